@@ -1,0 +1,184 @@
+/*
+ * agg — AllGather-GEMM consumer and GEMM-ReduceScatter reducer for MI355X (gfx950).
+ *
+ * C ABI of libagg.so.  Plain pointers and sizes only.  Unless a parameter says
+ * "host", every data pointer is a DEVICE pointer owned by the caller; the library
+ * owns only what symm_alloc creates (the symmetric staging buffer, the signal
+ * words and a few bookkeeping words).  Streams are hipStream_t passed as void*
+ * (NULL = the default stream).  All work is enqueued asynchronously on the
+ * caller's streams; only symm_alloc, symm_free and agg_status synchronise.
+ * Nothing here falls back to the CPU.
+ *
+ * Every function returns AGG_OK (0) or a negative AGG_ERR_* code and has no other
+ * effect when it fails; agg_strerror names a code.  Functions are not thread-safe
+ * on one context; different contexts are independent.
+ *
+ * Vocabulary (the paper's, Section 2.1 and Algorithms 1-3): W = WORLD_SIZE,
+ * rank = RANK, T = symmetric buffer, S = signal array, L = a rank's local shard.
+ */
+#ifndef AGG_H
+#define AGG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct agg_ctx agg_ctx;
+
+enum {
+    AGG_OK = 0,
+    AGG_ERR_INVALID_ARG = -1,       /* null pointer, negative size, rank outside [0, W) ... */
+    AGG_ERR_UNSUPPORTED_SHAPE = -2, /* K not a multiple of 32, M not a multiple of W, shard larger than T ... */
+    AGG_ERR_MISALIGNED = -3,        /* a pointer or leading dimension breaks the 16-byte rule */
+    AGG_ERR_HIP = -4,               /* a HIP runtime call failed (the HIP error is cleared) */
+    AGG_ERR_TIMEOUT = -5,           /* a kernel gave up waiting for a signal (reported by agg_status) */
+    AGG_ERR_NOMEM = -6
+};
+
+enum { AGG_BF16 = 0, AGG_F32 = 1 };          /* element type of an output matrix */
+enum { AGG_B_NK = 0,                         /* B stored [N][K], K contiguous (weight layout of a linear layer) */
+       AGG_B_KN = 1 };                       /* B stored [K][N], N contiguous */
+enum { AGG_PRODUCER_KERNEL = 0,              /* copy kernel on a few CUs, release-stores the signals */
+       AGG_PRODUCER_SDMA = 1,               /* copy engine (no compute units) + one 4-byte copy per signal */
+       AGG_PRODUCER_SKIP_LOCAL = 0x100 };    /* OR into mode: do not (re)copy the local shard in this call */
+
+/* One signal word per AGG_SIGNAL_STRIDE int32 (each signal owns a 128-byte line). */
+#define AGG_SIGNAL_STRIDE 32
+
+/* ------------------------------------------------------------------------------------------------
+ * Symmetric memory and signals (Section 2.1: symmetric memory, signal exchange).
+ *
+ * symm_alloc creates this rank's symmetric buffer T of world_size * shard_bytes bytes (shard r lives at
+ * byte offset r * shard_bytes, the layout of Algorithms 1 and 2) and n_signals signal words, all zero.
+ * A context carries an epoch, starting at 1: a signal counts as set when its value >= epoch, so
+ * signal_reset only has to advance the epoch (no device work, nothing to race with) and a signal left
+ * over from an earlier run can never satisfy a wait.  shard_bytes must be a multiple of 16.
+ * n_signals >= world_size; signals are grouped per shard: chunk c of shard r is signal
+ * r * (n_signals / world_size) + c, so n_signals must be a multiple of world_size.
+ * symm_alloc and symm_free synchronise the device.
+ */
+int symm_alloc(agg_ctx** ctx, int world_size, int rank, size_t shard_bytes, int n_signals);
+int symm_free(agg_ctx* ctx);
+void* symm_staging(agg_ctx* ctx);            /* device pointer to T, borrowed */
+int32_t* symm_signals(agg_ctx* ctx);         /* device pointer to S (signal i at S[i * AGG_SIGNAL_STRIDE]), borrowed */
+int symm_epoch(agg_ctx* ctx);                /* current epoch (host value) */
+
+/*
+ * Two streams the context owns, for the communication part and the computation part (Section 2.3: the host
+ * "launches the communication part and the computation part on different streams").  They are created
+ * back to back at symm_alloc so that they sit on different hardware queues: kernels of streams that share
+ * a hardware queue run one after the other, and a consumer launched ahead of its producer on such a pair
+ * would wait for signals that cannot come (its waits are bounded, so it would time out, not hang).
+ * Callers may use streams of their own instead; then they should launch the producer first.
+ */
+int symm_streams(agg_ctx* ctx, void** producer_stream, void** consumer_stream);
+
+/*
+ * "Reset all the signals" before every run of an overlapped function (Section 3.8, the autotuner's rule).
+ * Advances the epoch; calls issued afterwards wait for, and set, the new epoch.  The caller orders the
+ * previous run's kernels before the next run's producer (they share T).  `stream` is accepted for
+ * interface stability and unused.
+ */
+int signal_reset(agg_ctx* ctx, void* stream);
+
+/* Set signal `index` to the current epoch on `stream` (a 4-byte release store by a one-thread kernel). */
+int signal_set(agg_ctx* ctx, int index, void* stream);
+
+/*
+ * Bound every in-kernel wait: after `microseconds` without its signal a workgroup records a time-out,
+ * every workgroup of that launch stops waiting, and the launch drains (its output is then undefined).
+ * Default 2,000,000 (2 s).  0 is rejected: an unbounded wait can hang the GPU.
+ */
+int agg_set_wait_limit_us(agg_ctx* ctx, uint64_t microseconds);
+
+/* Synchronises the device, then returns AGG_OK, or AGG_ERR_TIMEOUT if any launch on this context
+ * since the last agg_status call gave up a wait (the record is cleared). */
+int agg_status(agg_ctx* ctx);
+
+/* ------------------------------------------------------------------------------------------------
+ * Emulated AllGather arrival (Algorithm 2, pull mode, seen from this rank; on one GPU the "remote"
+ * shards are other device buffers).
+ *
+ * remote_shards: HOST array of W device pointers; remote_shards[r] is rank r's local buffer L_r
+ * (shard_bytes each).  First L_rank is copied to T + rank*shard_bytes and its signals are set (unless mode
+ * carries AGG_PRODUCER_SKIP_LOCAL, for callers that deliver the shards over several calls); then, for
+ * each r in arrival_order (HOST array of n_arrivals ranks, each != rank, no repeats; NULL = the rotated
+ * order rank+1, rank+2, ... and n_arrivals is ignored), L_r is copied to T + r*shard_bytes chunk by chunk
+ * and each chunk's signal is set (release) once the chunk has landed.  Shards not listed never arrive.
+ * mode: AGG_PRODUCER_KERNEL uses `n_workgroups` workgroups (0 = default 32) whose registers fit beside
+ * the consumer's on every CU; AGG_PRODUCER_SDMA uses hipMemcpyAsync without compute units.
+ */
+int ag_producer_emulate(agg_ctx* ctx, const void* const* remote_shards, const int* arrival_order,
+                        int n_arrivals, int mode, int n_workgroups, void* producer_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * AllGather-GEMM consumer (Section 2.3 / Figure 4: a tiled GEMM whose tiles wait on the signals of the
+ * shards they read; Section 3.7: rank-rotated tile order, local shard first).
+ *
+ * C[M, N] = A[M, K] . B with A = T viewed as [M, K] bf16 row-major (lda = K; M = W * Ms, shard r = rows
+ * [r*Ms, (r+1)*Ms), so shard_bytes must equal Ms*K*2), B bf16 in the layout b_layout names with leading
+ * dimension ldb (elements), C row-major with leading dimension ldc (elements) of type c_dtype.
+ * Accumulation is fp32; bf16 output is rounded to nearest even from the fp32 accumulator.
+ * Each tile waits (acquire) for every signal covering its rows to reach the current epoch before its
+ * first load of A.  Requirements: K % 32 == 0, M % W == 0, ldb % 8 == 0, B 16-byte aligned,
+ * C aligned to its element size; M, N arbitrary (>= 0; 0 is a no-op).
+ */
+int ag_gemm(agg_ctx* ctx, int M, int N, int K,
+            const void* B, int ldb, int b_layout,
+            void* C, int ldc, int c_dtype, void* consumer_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * ReduceScatter reduction (Algorithm 3, stream 2): R = sum_{w=0}^{W-1} slot_w, fp32, in the order
+ * w = 0, 1, .., W-1 starting from +0, whatever the arrival order.  Before reading slot w the kernel waits
+ * for signal w * (n_signals / W) to reach the current epoch.
+ * slots: HOST array of W device pointers to fp32 [Ms, N] row-major (leading dimension N).
+ * R: [Ms, N] of r_dtype, leading dimension ldr.  Ms * N must be a multiple of 4; slots 16-byte aligned.
+ */
+int rs_reduce(agg_ctx* ctx, int Ms, int N, const float* const* slots,
+              void* R, int ldr, int r_dtype, int n_workgroups, void* stream);
+
+/*
+ * GEMM + ReduceScatter for one rank (Section 3.3, Algorithm 3; Section 4.1 "GEMM ReduceScatter").
+ * Enqueues on gemm_stream the local partial product P[M, N] = A_local[M, Klocal] . B_local (bf16 in, fp32
+ * out, un-gated), computing this rank's row slice [rank*Ms, (rank+1)*Ms) first and writing it straight
+ * into slots[rank]; when that slice is complete its signal is set (the producer signal of Algorithm 3).
+ * The other rows go to P_other (fp32 [M, N], leading dimension N; rows of the own slice are not written;
+ * may be NULL to skip computing them).  Enqueues on reduce_stream the reduction of rs_reduce, which
+ * waits for every slot's signal.  Peers' slots "arrive" when the caller sets their signals
+ * (signal_set, or a producer of the caller's own).
+ */
+int gemm_rs(agg_ctx* ctx, int M, int N, int Klocal,
+            const void* A_local, int lda, const void* B_local, int ldb, int b_layout,
+            const float* const* slots, float* P_other,
+            void* R, int ldr, int r_dtype, void* gemm_stream, void* reduce_stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * MoE AllGather grouped GEMM (Section 4.1 "AllGather MoE", Table 4; tensor parallel).
+ * T holds the gathered tokens X[Ttok, K] (shard r = tokens [r*tpr, (r+1)*tpr)).  topk_ids: DEVICE int32
+ * [Ttok, topk], distinct experts per token.  The (token, slot) pairs are ordered by (expert, token, slot);
+ * Y[p, :] = X[token(p), :] . W_expert(p) for the p-th pair, Y [Ttok*topk, N] row-major of y_dtype.
+ * weights: bf16 [E][N][K] (K contiguous per expert).  sorted_token / sorted_expert_offsets are DEVICE
+ * outputs the call fills (int32 [Ttok*topk] and int32 [E+1]) and then uses; the caller may read them.
+ * Each tile waits for the signals of every shard its gathered tokens come from.
+ */
+int ag_moe_gemm(agg_ctx* ctx, int Ttok, int topk, int E, int N, int K,
+                const int32_t* topk_ids, const void* weights,
+                int32_t* sorted_token, int32_t* sorted_expert_offsets,
+                void* Y, int ldy, int y_dtype, void* stream);
+
+/* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 256x256,
+ * 2 = 128x128.  A tuning knob (Section 3.8); every shape gives the same result up to fp32 summation order. */
+int agg_set_tile_config(agg_ctx* ctx, int tile_config);
+
+const char* agg_strerror(int code);
+
+/* Device facts the bench reports against (compute units, peak clock in kHz). */
+int agg_device_info(int* compute_units, int* clock_khz);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGG_H */

@@ -337,11 +337,11 @@ done:
     return rc;
 }
 
-/* -------------------------------------------------- Section 3.4 sizing bound */
+/* -------------------------------------------------- Section 3.5 sizing bound */
 
 /*
  * Bandwidth (GB/s) the local reduction must sustain for perfect overlap in the
- * cross-node ReduceScatter analysis of Section 3.4: with volume B per slice, the
+ * cross-node ReduceScatter analysis of Section 3.5: with volume B per slice, the
  * intra-node scatter takes (W-1) B / link, the P2P send B / nic, and the
  * reduction (reads W slices, writes one) must fit in the difference.
  */

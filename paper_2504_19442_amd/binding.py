@@ -1,0 +1,221 @@
+"""ctypes binding with the names of include/agg.h.  Argument marshalling only.
+
+Pointers may be given as integers (device addresses) or as objects with a
+`data_ptr()` method (torch tensors); streams as integers (hipStream_t), objects
+with a `cuda_stream` attribute (torch.cuda.Stream), or None for the default
+stream.  A negative return code raises AggError.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+__all__ = [
+    "AggError", "Ctx", "symm_alloc", "signal_reset", "signal_set", "ag_producer_emulate", "ag_gemm",
+    "rs_reduce", "gemm_rs", "ag_moe_gemm", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
+    "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_SKIP_LOCAL", "SIGNAL_STRIDE",
+    "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM",
+    "EXPORTS",
+]
+
+BF16, F32 = 0, 1
+B_NK, B_KN = 0, 1
+PRODUCER_KERNEL, PRODUCER_SDMA, PRODUCER_SKIP_LOCAL = 0, 1, 0x100
+SIGNAL_STRIDE = 32
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT, ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
+
+# every symbol include/agg.h declares
+EXPORTS = [
+    "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
+    "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs",
+    "ag_moe_gemm", "agg_set_tile_config", "agg_strerror", "agg_device_info",
+]
+
+
+def lib_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libagg.so")
+
+
+_LIB = None
+
+
+def _lib() -> C.CDLL:
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(
+                f"{path} is missing: build the HIP extension first (python -c 'import __graft_entry__ as g; g.build()'). "
+                "There is no CPU fallback.")
+        L = C.CDLL(path)
+        vp, i32, i64, u64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint64, C.c_size_t
+        L.symm_alloc.argtypes = [C.POINTER(vp), i32, i32, sz, i32]
+        L.symm_free.argtypes = [vp]
+        L.symm_staging.argtypes = [vp]
+        L.symm_staging.restype = vp
+        L.symm_signals.argtypes = [vp]
+        L.symm_signals.restype = vp
+        L.symm_epoch.argtypes = [vp]
+        L.symm_streams.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
+        L.signal_reset.argtypes = [vp, vp]
+        L.signal_set.argtypes = [vp, i32, vp]
+        L.agg_set_wait_limit_us.argtypes = [vp, u64]
+        L.agg_set_tile_config.argtypes = [vp, i32]
+        L.agg_status.argtypes = [vp]
+        L.ag_producer_emulate.argtypes = [vp, C.POINTER(vp), C.POINTER(i32), i32, i32, i32, vp]
+        L.ag_gemm.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, i32, i32, vp]
+        L.rs_reduce.argtypes = [vp, i32, i32, C.POINTER(vp), vp, i32, i32, i32, vp]
+        L.gemm_rs.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32, i32, C.POINTER(vp), vp, vp, i32, i32, vp, vp]
+        L.ag_moe_gemm.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32, vp]
+        L.agg_strerror.argtypes = [i32]
+        L.agg_strerror.restype = C.c_char_p
+        L.agg_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32)]
+        for name in EXPORTS:
+            if name not in ("symm_staging", "symm_signals", "agg_strerror"):
+                getattr(L, name).restype = i32
+        _LIB = L
+    return _LIB
+
+
+class AggError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {agg_strerror(code)} ({code})")
+
+
+def agg_strerror(code: int) -> str:
+    return _lib().agg_strerror(int(code)).decode()
+
+
+def _check(rc: int, what: str) -> int:
+    if rc < 0:
+        raise AggError(rc, what)
+    return rc
+
+
+def _ptr(x) -> C.c_void_p:
+    if x is None:
+        return C.c_void_p(None)
+    if hasattr(x, "data_ptr"):
+        return C.c_void_p(x.data_ptr())
+    return C.c_void_p(int(x))
+
+
+def _stream(s) -> C.c_void_p:
+    if s is None:
+        return C.c_void_p(None)
+    if hasattr(s, "cuda_stream"):
+        return C.c_void_p(s.cuda_stream)
+    return C.c_void_p(int(s))
+
+
+def _ptr_array(items):
+    return (C.c_void_p * len(items))(*[_ptr(i).value for i in items])
+
+
+class Ctx:
+    """Owner of one agg_ctx* (symmetric buffer T, signals S, epoch)."""
+
+    def __init__(self, handle: int, world_size: int, rank: int, shard_bytes: int, n_signals: int):
+        self.handle = C.c_void_p(handle)
+        self.world_size, self.rank, self.shard_bytes, self.n_signals = world_size, rank, shard_bytes, n_signals
+
+    @property
+    def staging(self) -> int:
+        return int(_lib().symm_staging(self.handle) or 0)
+
+    @property
+    def signals(self) -> int:
+        return int(_lib().symm_signals(self.handle) or 0)
+
+    def streams(self):
+        """(producer_stream, consumer_stream) as integer hipStream_t handles owned by the context."""
+        p, c = C.c_void_p(None), C.c_void_p(None)
+        _check(_lib().symm_streams(self.handle, C.byref(p), C.byref(c)), "symm_streams")
+        return int(p.value), int(c.value)
+
+    @property
+    def epoch(self) -> int:
+        return _check(_lib().symm_epoch(self.handle), "symm_epoch")
+
+    def set_wait_limit_us(self, us: int) -> None:
+        _check(_lib().agg_set_wait_limit_us(self.handle, int(us)), "agg_set_wait_limit_us")
+
+    def set_tile_config(self, cfg: int) -> None:
+        _check(_lib().agg_set_tile_config(self.handle, int(cfg)), "agg_set_tile_config")
+
+    def free(self) -> None:
+        if self.handle:
+            _check(_lib().symm_free(self.handle), "symm_free")
+            self.handle = C.c_void_p(None)
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.free()
+
+
+def symm_alloc(world_size: int, rank: int, shard_bytes: int, n_signals: int | None = None) -> Ctx:
+    n_signals = world_size if n_signals is None else n_signals
+    h = C.c_void_p(None)
+    _check(_lib().symm_alloc(C.byref(h), world_size, rank, shard_bytes, n_signals), "symm_alloc")
+    return Ctx(h.value, world_size, rank, shard_bytes, n_signals)
+
+
+def signal_reset(ctx: Ctx, stream=None) -> None:
+    _check(_lib().signal_reset(ctx.handle, _stream(stream)), "signal_reset")
+
+
+def signal_set(ctx: Ctx, index: int, stream=None) -> None:
+    _check(_lib().signal_set(ctx.handle, int(index), _stream(stream)), "signal_set")
+
+
+def agg_status(ctx: Ctx) -> int:
+    """AGG_OK or ERR_TIMEOUT (not raised: a time-out is a reportable state)."""
+    rc = _lib().agg_status(ctx.handle)
+    if rc not in (OK, ERR_TIMEOUT):
+        raise AggError(rc, "agg_status")
+    return rc
+
+
+def ag_producer_emulate(ctx: Ctx, remote_shards, arrival_order=None, mode: int = PRODUCER_KERNEL,
+                        n_workgroups: int = 0, stream=None) -> None:
+    ptrs = _ptr_array(remote_shards)
+    if arrival_order is None:
+        order, n = None, 0
+    else:
+        n = len(arrival_order)
+        order = (C.c_int * max(n, 1))(*arrival_order)
+    _check(_lib().ag_producer_emulate(ctx.handle, ptrs, order, n, mode, n_workgroups, _stream(stream)),
+           "ag_producer_emulate")
+
+
+def ag_gemm(ctx: Ctx, M: int, N: int, K: int, B, ldb: int, b_layout: int, Cout, ldc: int, c_dtype: int,
+            stream=None) -> None:
+    _check(_lib().ag_gemm(ctx.handle, M, N, K, _ptr(B), ldb, b_layout, _ptr(Cout), ldc, c_dtype, _stream(stream)),
+           "ag_gemm")
+
+
+def rs_reduce(ctx: Ctx, Ms: int, N: int, slots, R, ldr: int, r_dtype: int, n_workgroups: int = 0, stream=None) -> None:
+    _check(_lib().rs_reduce(ctx.handle, Ms, N, _ptr_array(slots), _ptr(R), ldr, r_dtype, n_workgroups, _stream(stream)),
+           "rs_reduce")
+
+
+def gemm_rs(ctx: Ctx, M: int, N: int, Klocal: int, A_local, lda: int, B_local, ldb: int, b_layout: int, slots,
+            P_other, R, ldr: int, r_dtype: int, gemm_stream=None, reduce_stream=None) -> None:
+    _check(_lib().gemm_rs(ctx.handle, M, N, Klocal, _ptr(A_local), lda, _ptr(B_local), ldb, b_layout,
+                          _ptr_array(slots), _ptr(P_other), _ptr(R), ldr, r_dtype, _stream(gemm_stream),
+                          _stream(reduce_stream)), "gemm_rs")
+
+
+def ag_moe_gemm(ctx: Ctx, Ttok: int, topk: int, E: int, N: int, K: int, topk_ids, weights, sorted_token,
+                sorted_expert_offsets, Y, ldy: int, y_dtype: int, stream=None) -> None:
+    _check(_lib().ag_moe_gemm(ctx.handle, Ttok, topk, E, N, K, _ptr(topk_ids), _ptr(weights), _ptr(sorted_token),
+                              _ptr(sorted_expert_offsets), _ptr(Y), ldy, y_dtype, _stream(stream)), "ag_moe_gemm")
+
+
+def agg_device_info():
+    cu, khz = C.c_int(0), C.c_int(0)
+    _check(_lib().agg_device_info(C.byref(cu), C.byref(khz)), "agg_device_info")
+    return cu.value, khz.value

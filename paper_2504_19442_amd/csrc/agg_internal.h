@@ -1,0 +1,107 @@
+// Internal declarations shared by the translation units of libagg.so (HIP path only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/agg.h"
+
+namespace agg {
+
+constexpr int kMaxWorld = 64;          // kernel-argument arrays are sized for this many ranks
+constexpr int kSignalStride = AGG_SIGNAL_STRIDE;
+
+// What one GEMM launch needs.  A is row-major [M][K] bf16 (optionally gathered through row_index),
+// B is [N][K] bf16 (K contiguous), C row-major.
+struct GemmParams {
+    const uint16_t* A;
+    const uint16_t* B;
+    void* C;              // rows outside [own_lo, own_hi) (or every row if C_own == nullptr)
+    void* C_own;          // GEMM-RS: rows [own_lo, own_hi) go here, at row index (row - own_lo)
+    long long lda, ldb, ldc, ldc_own;
+    int M, N, K;
+    int c_is_f32;
+    // tile schedule (Section 3.7: rank-rotated order, local shard first)
+    int tiles_m, tiles_n;
+    int panel_m;          // m-tiles per panel (a panel = the tiles of one shard step)
+    int group_n;          // n-tiles per L2 block inside a panel
+    int m_tile_start;     // m-tile holding this rank's first row
+    // signals (nullptr = un-gated)
+    const int* flags;
+    int epoch;
+    int rows_per_flag;    // rows of A covered by one signal
+    int n_flags;
+    long long wait_ticks; // bound of a wait, in wall-clock ticks
+    int* err;             // device word: set to 1 when a wait is given up
+    // GEMM-RS producer signal: tiles touching [own_lo, own_hi) count up done_ctr; the last one sets done_flag
+    int own_lo, own_hi;
+    int* done_ctr;
+    int done_target;
+    int* done_flag;
+};
+
+enum TileConfig { TILE_256x224 = 0, TILE_256x256 = 1, TILE_128x128 = 2, TILE_CONFIGS };
+
+struct TileShape { int bm, bn; };
+inline TileShape tile_shape(int cfg)
+{
+    switch (cfg) {
+        case TILE_256x224: return {256, 224};
+        case TILE_256x256: return {256, 256};
+        default: return {128, 128};
+    }
+}
+
+hipError_t launch_gemm(const GemmParams& p, int cfg, int grid, hipStream_t stream);
+
+struct ProducerArgs {
+    const void* src[kMaxWorld];   // src[j] = local buffer of the j-th shard to arrive
+    int rank_of[kMaxWorld];       // its rank (destination slot in T)
+    int n_jobs;
+    char* T;
+    long long shard_bytes;
+    long long chunk_bytes;
+    int chunks_per_shard;
+    int* flags;
+    int* counters;
+    int epoch;
+};
+hipError_t launch_producer(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
+hipError_t launch_signal_set(int* flag, int value, hipStream_t stream);
+
+struct ReduceArgs {
+    const float* slot[kMaxWorld];
+    int W;
+    long long n_vec4;             // number of float4 elements
+    long long row_vec4;           // float4 per row (N / 4) when ldr != N, else 0
+    void* R;
+    long long ldr;
+    int r_is_f32;
+    int N;
+    const int* flags;
+    int flag_step;                // signal index of slot w = w * flag_step
+    int epoch;
+    long long wait_ticks;
+    int* err;
+};
+hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream);
+
+}  // namespace agg
+
+struct agg_ctx {
+    int W, rank;
+    size_t shard_bytes;
+    int n_signals;
+    int epoch;
+    uint64_t wait_limit_us;
+    long long wall_khz;
+    int num_cus;
+    char* staging;       // T
+    int* signals;        // S, n_signals * stride
+    int* counters;       // per-signal arrival counters (producer), + GEMM-RS tile counter
+    int* err;            // time-out record
+    int* epoch_word;     // device copy of the epoch (source of the SDMA signal copies)
+    int device;
+    int tile_config;     // -1 = automatic
+    hipStream_t producer_stream, consumer_stream;
+};

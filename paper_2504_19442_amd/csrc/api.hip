@@ -1,0 +1,430 @@
+// C ABI of libagg.so: argument checks, context bookkeeping and launches.  No arithmetic of the
+// method happens on the host; every step runs in the HIP kernels of this library.
+#include "agg_internal.h"
+
+#include <new>
+
+using namespace agg;
+
+namespace {
+
+inline int hip_fail(hipError_t e)
+{
+    if (e == hipSuccess) return AGG_OK;
+    (void)hipGetLastError();
+    return e == hipErrorOutOfMemory ? AGG_ERR_NOMEM : AGG_ERR_HIP;
+}
+
+#define HIP_TRY(x)                         \
+    do {                                   \
+        int rc_ = hip_fail((x));           \
+        if (rc_ != AGG_OK) return rc_;     \
+    } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline long long wait_ticks(const agg_ctx* c)
+{
+    return (long long)((double)c->wall_khz * (double)c->wait_limit_us / 1000.0);
+}
+
+// Pick the tile shape with the smallest estimated time: waves of tiles over the CUs times the cost of a
+// tile (its area over a rough efficiency of the shape).
+int choose_tile(const agg_ctx* c, int M, int N)
+{
+    if (c->tile_config >= 0) return c->tile_config;
+    const int cand[2] = {TILE_256x224, TILE_128x128};
+    const double eff[2] = {1.0, 0.75};
+    int best = cand[0];
+    double best_cost = 1e300;
+    for (int i = 0; i < 2; ++i) {
+        const TileShape t = tile_shape(cand[i]);
+        const long long tiles = (long long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+        const long long waves = (tiles + c->num_cus - 1) / c->num_cus;
+        const double cost = (double)waves * t.bm * t.bn / eff[i];
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = cand[i];
+        }
+    }
+    return best;
+}
+
+// Fill the schedule fields: panels of `rows_per_shard` rows starting at the panel of `first_row`.
+void fill_schedule(GemmParams& p, int cfg, int rows_per_shard, int first_row)
+{
+    const TileShape t = tile_shape(cfg);
+    p.tiles_m = (p.M + t.bm - 1) / t.bm;
+    p.tiles_n = (p.N + t.bn - 1) / t.bn;
+    int pm = rows_per_shard / t.bm;
+    if (pm < 1) pm = 1;
+    if (pm > 32) pm = 32;
+    p.panel_m = pm;
+    p.group_n = 32 / pm > 0 ? 32 / pm : 1;
+    p.m_tile_start = p.tiles_m > 0 ? (first_row / t.bm) % p.tiles_m : 0;
+}
+
+int check_gemm_operands(int M, int N, int K, const void* B, int ldb, int b_layout, const void* C, int ldc, int c_dtype)
+{
+    if (M < 0 || N < 0 || K < 0) return AGG_ERR_INVALID_ARG;
+    if (c_dtype != AGG_BF16 && c_dtype != AGG_F32) return AGG_ERR_INVALID_ARG;
+    if (b_layout != AGG_B_NK && b_layout != AGG_B_KN) return AGG_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return AGG_OK;
+    if (!B || !C) return AGG_ERR_INVALID_ARG;
+    if (b_layout != AGG_B_NK) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (K == 0 || K % 32 != 0 || K > (1 << 21)) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (ldb < K || ldc < N) return AGG_ERR_INVALID_ARG;
+    if (ldb % 8 != 0 || !aligned16(B)) return AGG_ERR_MISALIGNED;
+    if (reinterpret_cast<uintptr_t>(C) % (c_dtype == AGG_F32 ? 4 : 2) != 0) return AGG_ERR_MISALIGNED;
+    return AGG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int n_signals)
+{
+    if (!out || world_size < 1 || world_size > kMaxWorld || rank < 0 || rank >= world_size) return AGG_ERR_INVALID_ARG;
+    if (n_signals < world_size || n_signals % world_size != 0 || n_signals > (1 << 20)) return AGG_ERR_INVALID_ARG;
+    if (shard_bytes == 0 || shard_bytes % 16 != 0) return AGG_ERR_MISALIGNED;
+    agg_ctx* c = new (std::nothrow) agg_ctx();
+    if (!c) return AGG_ERR_NOMEM;
+    c->W = world_size;
+    c->rank = rank;
+    c->shard_bytes = shard_bytes;
+    c->n_signals = n_signals;
+    c->epoch = 1;
+    c->wait_limit_us = 2000000;
+    c->tile_config = -1;
+    int rc = AGG_OK;
+    hipDeviceProp_t prop;
+    int khz = 0;
+    const size_t sig_bytes = (size_t)n_signals * kSignalStride * sizeof(int);
+    const size_t ctr_bytes = ((size_t)n_signals + 32) * sizeof(int);
+    if ((rc = hip_fail(hipGetDevice(&c->device))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipGetDeviceProperties(&prop, c->device))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device))) != AGG_OK) goto fail;
+    c->num_cus = prop.multiProcessorCount;
+    c->wall_khz = khz > 0 ? khz : 100000;
+    if ((rc = hip_fail(hipMalloc((void**)&c->staging, (size_t)world_size * shard_bytes))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMalloc((void**)&c->signals, sig_bytes))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMalloc((void**)&c->counters, ctr_bytes))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMalloc((void**)&c->err, 256))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMalloc((void**)&c->epoch_word, 256))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMemset(c->signals, 0, sig_bytes))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMemset(c->counters, 0, ctr_bytes))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMemset(c->err, 0, 256))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMemset(c->epoch_word, 0, 256))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipStreamCreateWithFlags(&c->producer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipStreamCreateWithFlags(&c->consumer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) goto fail;
+    *out = c;
+    return AGG_OK;
+fail:
+    symm_free(c);
+    return rc;
+}
+
+int symm_free(agg_ctx* c)
+{
+    if (!c) return AGG_ERR_INVALID_ARG;
+    (void)hipDeviceSynchronize();
+    if (c->producer_stream) (void)hipStreamDestroy(c->producer_stream);
+    if (c->consumer_stream) (void)hipStreamDestroy(c->consumer_stream);
+    if (c->staging) (void)hipFree(c->staging);
+    if (c->signals) (void)hipFree(c->signals);
+    if (c->counters) (void)hipFree(c->counters);
+    if (c->err) (void)hipFree(c->err);
+    if (c->epoch_word) (void)hipFree(c->epoch_word);
+    (void)hipGetLastError();
+    delete c;
+    return AGG_OK;
+}
+
+void* symm_staging(agg_ctx* c) { return c ? c->staging : nullptr; }
+int32_t* symm_signals(agg_ctx* c) { return c ? c->signals : nullptr; }
+int symm_epoch(agg_ctx* c) { return c ? c->epoch : AGG_ERR_INVALID_ARG; }
+
+int symm_streams(agg_ctx* c, void** producer_stream, void** consumer_stream)
+{
+    if (!c || !producer_stream || !consumer_stream) return AGG_ERR_INVALID_ARG;
+    *producer_stream = (void*)c->producer_stream;
+    *consumer_stream = (void*)c->consumer_stream;
+    return AGG_OK;
+}
+
+int signal_reset(agg_ctx* c, void* /*stream*/)
+{
+    if (!c) return AGG_ERR_INVALID_ARG;
+    if (c->epoch >= 0x7ffffff0) return AGG_ERR_INVALID_ARG;   // 2^31 runs: allocate a new context
+    c->epoch += 1;
+    return AGG_OK;
+}
+
+int signal_set(agg_ctx* c, int index, void* stream)
+{
+    if (!c || index < 0 || index >= c->n_signals) return AGG_ERR_INVALID_ARG;
+    return hip_fail(launch_signal_set(c->signals + (size_t)index * kSignalStride, c->epoch, (hipStream_t)stream));
+}
+
+int agg_set_wait_limit_us(agg_ctx* c, uint64_t us)
+{
+    if (!c || us == 0 || us > 600ull * 1000 * 1000) return AGG_ERR_INVALID_ARG;
+    c->wait_limit_us = us;
+    return AGG_OK;
+}
+
+int agg_set_tile_config(agg_ctx* c, int cfg)
+{
+    if (!c || cfg < -1 || cfg >= TILE_CONFIGS) return AGG_ERR_INVALID_ARG;
+    c->tile_config = cfg;
+    return AGG_OK;
+}
+
+int agg_status(agg_ctx* c)
+{
+    if (!c) return AGG_ERR_INVALID_ARG;
+    HIP_TRY(hipDeviceSynchronize());
+    int h = 0;
+    HIP_TRY(hipMemcpy(&h, c->err, sizeof h, hipMemcpyDeviceToHost));
+    if (h != 0) {
+        HIP_TRY(hipMemset(c->err, 0, sizeof h));
+        HIP_TRY(hipDeviceSynchronize());
+        return AGG_ERR_TIMEOUT;
+    }
+    return AGG_OK;
+}
+
+int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int* arrival_order, int n_arrivals,
+                        int mode, int n_workgroups, void* producer_stream)
+{
+    if (!c || !remote_shards) return AGG_ERR_INVALID_ARG;
+    const bool skip_local = (mode & AGG_PRODUCER_SKIP_LOCAL) != 0;
+    mode &= ~AGG_PRODUCER_SKIP_LOCAL;
+    if (mode != AGG_PRODUCER_KERNEL && mode != AGG_PRODUCER_SDMA) return AGG_ERR_INVALID_ARG;
+    if (n_workgroups < 0 || n_workgroups > 4096) return AGG_ERR_INVALID_ARG;
+    const int W = c->W;
+    if (arrival_order && (n_arrivals < 0 || n_arrivals > W - 1)) return AGG_ERR_INVALID_ARG;
+    const int cps = c->n_signals / W;
+    if (c->shard_bytes % ((size_t)cps * 16) != 0) return AGG_ERR_MISALIGNED;
+    ProducerArgs a{};
+    bool used[kMaxWorld] = {false};
+    a.n_jobs = 0;
+    if (!skip_local) a.rank_of[a.n_jobs++] = c->rank;   // the local copy comes first (Algorithm 2)
+    used[c->rank] = true;
+    const int n = arrival_order ? n_arrivals : W - 1;
+    for (int j = 0; j < n; ++j) {
+        const int r = arrival_order ? arrival_order[j] : (c->rank + 1 + j) % W;
+        if (r < 0 || r >= W || used[r]) return AGG_ERR_INVALID_ARG;
+        used[r] = true;
+        a.rank_of[a.n_jobs++] = r;
+    }
+    for (int j = 0; j < a.n_jobs; ++j) {
+        a.src[j] = remote_shards[a.rank_of[j]];
+        if (!a.src[j]) return AGG_ERR_INVALID_ARG;
+        if (!aligned16(a.src[j])) return AGG_ERR_MISALIGNED;
+    }
+    if (a.n_jobs == 0) return AGG_OK;
+    a.T = c->staging;
+    a.shard_bytes = (long long)c->shard_bytes;
+    a.chunks_per_shard = cps;
+    a.chunk_bytes = (long long)(c->shard_bytes / cps);
+    a.flags = c->signals;
+    a.counters = c->counters;
+    a.epoch = c->epoch;
+    hipStream_t st = (hipStream_t)producer_stream;
+    if (mode == AGG_PRODUCER_KERNEL) {
+        const int nwg = n_workgroups > 0 ? n_workgroups : 32;
+        return hip_fail(launch_producer(a, nwg, st));
+    }
+    // copy engine: one transfer per chunk, then "another data transfer solely for signals" (Section 3.6)
+    HIP_TRY(launch_signal_set(c->epoch_word, c->epoch, st));
+    for (int j = 0; j < a.n_jobs; ++j) {
+        const int r = a.rank_of[j];
+        for (int ch = 0; ch < cps; ++ch) {
+            const size_t off = (size_t)ch * a.chunk_bytes;
+            HIP_TRY(hipMemcpyAsync(c->staging + (size_t)r * c->shard_bytes + off, (const char*)a.src[j] + off,
+                                   (size_t)a.chunk_bytes, hipMemcpyDeviceToDeviceNoCU, st));
+            HIP_TRY(hipMemcpyAsync(c->signals + (size_t)(r * cps + ch) * kSignalStride, c->epoch_word, sizeof(int),
+                                   hipMemcpyDeviceToDeviceNoCU, st));
+        }
+    }
+    return AGG_OK;
+}
+
+int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layout, void* C, int ldc, int c_dtype,
+            void* consumer_stream)
+{
+    if (!c) return AGG_ERR_INVALID_ARG;
+    int rc = check_gemm_operands(M, N, K, B, ldb, b_layout, C, ldc, c_dtype);
+    if (rc != AGG_OK) return rc;
+    if (M % c->W != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0 || N == 0) return AGG_OK;
+    const int Ms = M / c->W;
+    if ((size_t)Ms * K * 2 != c->shard_bytes) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const int cps = c->n_signals / c->W;
+    if (Ms % cps != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    GemmParams p{};
+    p.A = (const uint16_t*)c->staging;
+    p.B = (const uint16_t*)B;
+    p.C = C;
+    p.lda = K;
+    p.ldb = ldb;
+    p.ldc = ldc;
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    p.c_is_f32 = c_dtype == AGG_F32;
+    const int cfg = choose_tile(c, M, N);
+    fill_schedule(p, cfg, Ms, c->rank * Ms);
+    p.flags = c->signals;
+    p.epoch = c->epoch;
+    p.rows_per_flag = Ms / cps;
+    p.n_flags = c->n_signals;
+    p.wait_ticks = wait_ticks(c);
+    p.err = c->err;
+    const long long tiles = (long long)p.tiles_m * p.tiles_n;
+    const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
+    return hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)consumer_stream));
+}
+
+int rs_reduce(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int ldr, int r_dtype, int n_workgroups,
+              void* stream)
+{
+    if (!c || !slots || Ms < 0 || N < 0 || n_workgroups < 0 || n_workgroups > 65536) return AGG_ERR_INVALID_ARG;
+    if (r_dtype != AGG_BF16 && r_dtype != AGG_F32) return AGG_ERR_INVALID_ARG;
+    if (Ms == 0 || N == 0) return AGG_OK;
+    if (!R || ldr < N) return AGG_ERR_INVALID_ARG;
+    const long long n = (long long)Ms * N;
+    if (n % 4 != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (ldr != N && (N % 4 != 0)) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const int esz = r_dtype == AGG_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(R) % (4 * esz) != 0 || (ldr != N && ldr % 4 != 0)) return AGG_ERR_MISALIGNED;
+    ReduceArgs a{};
+    a.W = c->W;
+    for (int w = 0; w < c->W; ++w) {
+        if (!slots[w]) return AGG_ERR_INVALID_ARG;
+        if (!aligned16(slots[w])) return AGG_ERR_MISALIGNED;
+        a.slot[w] = slots[w];
+    }
+    a.n_vec4 = n / 4;
+    a.row_vec4 = (ldr != N) ? N / 4 : 0;
+    a.R = R;
+    a.ldr = ldr;
+    a.r_is_f32 = r_dtype == AGG_F32;
+    a.N = N;
+    a.flags = c->signals;
+    a.flag_step = c->n_signals / c->W;
+    a.epoch = c->epoch;
+    a.wait_ticks = wait_ticks(c);
+    a.err = c->err;
+    int nwg = n_workgroups;
+    if (nwg == 0) {
+        const long long need = (a.n_vec4 + 256 * 4 - 1) / (256 * 4);
+        nwg = (int)(need < (long long)c->num_cus * 8 ? need : (long long)c->num_cus * 8);
+        if (nwg < 1) nwg = 1;
+    }
+    return hip_fail(launch_reduce(a, nwg, (hipStream_t)stream));
+}
+
+int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, const void* B_local, int ldb, int b_layout,
+            const float* const* slots, float* P_other, void* R, int ldr, int r_dtype, void* gemm_stream,
+            void* reduce_stream)
+{
+    if (!c || !slots) return AGG_ERR_INVALID_ARG;
+    if (M % c->W != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const int Ms = M / c->W;
+    if (M == 0 || N == 0) return AGG_OK;
+    if (!slots[c->rank]) return AGG_ERR_INVALID_ARG;
+    int rc = check_gemm_operands(M, N, Kl, B_local, ldb, b_layout, slots[c->rank], N, AGG_F32);
+    if (rc != AGG_OK) return rc;
+    if (!A_local || lda < Kl) return AGG_ERR_INVALID_ARG;
+    if (lda % 8 != 0 || !aligned16(A_local)) return AGG_ERR_MISALIGNED;
+    // validate the reduction's arguments before anything is enqueued
+    if (!R || ldr < N || (r_dtype != AGG_BF16 && r_dtype != AGG_F32)) return AGG_ERR_INVALID_ARG;
+    if (((long long)Ms * N) % 4 != 0 || (ldr != N && N % 4 != 0)) return AGG_ERR_UNSUPPORTED_SHAPE;
+    for (int w = 0; w < c->W; ++w)
+        if (!slots[w] || !aligned16(slots[w])) return slots[w] ? AGG_ERR_MISALIGNED : AGG_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(R) % (4 * (r_dtype == AGG_F32 ? 4 : 2)) != 0 || (ldr != N && ldr % 4 != 0))
+        return AGG_ERR_MISALIGNED;
+
+    const int own_lo = c->rank * Ms, own_hi = own_lo + Ms;
+    GemmParams p{};
+    p.B = (const uint16_t*)B_local;
+    p.lda = lda;
+    p.ldb = ldb;
+    p.N = N;
+    p.K = Kl;
+    p.c_is_f32 = 1;
+    p.epoch = c->epoch;
+    p.err = c->err;
+    p.wait_ticks = wait_ticks(c);
+    int cfg;
+    if (P_other) {
+        p.A = (const uint16_t*)A_local;
+        p.M = M;
+        p.C = P_other;
+        p.ldc = N;
+        p.C_own = (void*)slots[c->rank];
+        p.ldc_own = N;
+        p.own_lo = own_lo;
+        p.own_hi = own_hi;
+        cfg = choose_tile(c, M, N);
+        fill_schedule(p, cfg, Ms, own_lo);
+    } else {
+        p.A = (const uint16_t*)A_local + (long long)own_lo * lda;
+        p.M = Ms;
+        p.C = (void*)slots[c->rank];
+        p.ldc = N;
+        p.own_lo = 0;
+        p.own_hi = Ms;
+        cfg = choose_tile(c, Ms, N);
+        fill_schedule(p, cfg, Ms, 0);
+    }
+    {
+        const TileShape t = tile_shape(cfg);
+        const int lo = p.own_lo / t.bm, hi = (p.own_hi - 1) / t.bm;
+        p.done_target = (hi - lo + 1) * p.tiles_n;
+        p.done_ctr = c->counters + c->n_signals;          // a counter of its own, after the producer's
+        p.done_flag = c->signals + (size_t)c->rank * (c->n_signals / c->W) * kSignalStride;
+    }
+    const long long tiles = (long long)p.tiles_m * p.tiles_n;
+    const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
+    rc = hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)gemm_stream));
+    if (rc != AGG_OK) return rc;
+    return rs_reduce(c, Ms, N, slots, R, ldr, r_dtype, 0, reduce_stream);
+}
+
+int ag_moe_gemm(agg_ctx*, int, int, int, int, int, const int32_t*, const void*, int32_t*, int32_t*, void*, int, int,
+                void*)
+{
+    return AGG_ERR_UNSUPPORTED_SHAPE;
+}
+
+const char* agg_strerror(int code)
+{
+    switch (code) {
+        case AGG_OK: return "ok";
+        case AGG_ERR_INVALID_ARG: return "invalid argument";
+        case AGG_ERR_UNSUPPORTED_SHAPE: return "unsupported shape or layout";
+        case AGG_ERR_MISALIGNED: return "misaligned pointer or leading dimension";
+        case AGG_ERR_HIP: return "HIP runtime error";
+        case AGG_ERR_TIMEOUT: return "a kernel gave up waiting for a signal";
+        case AGG_ERR_NOMEM: return "out of memory";
+        default: return "unknown error";
+    }
+}
+
+int agg_device_info(int* compute_units, int* clock_khz)
+{
+    int dev = 0;
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipGetDeviceProperties(&prop, dev));
+    if (compute_units) *compute_units = prop.multiProcessorCount;
+    if (clock_khz) *clock_khz = prop.clockRate;
+    return AGG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,229 @@
+"""GPU parity: the HIP AllGather-GEMM consumer against the CPU oracle, through the C ABI."""
+import itertools
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2504_19442_amd as agg
+import workloads as wl
+from gpu_util import AgGemmRun, bits_to_f64, host_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def check_f32(C_gpu: np.ndarray, C_ref: np.ndarray, K: int):
+    """The contract's bar: relative Frobenius error <= 1e-4 and max abs error <= 1e-3 * sqrt(K)."""
+    assert np.all(np.isfinite(C_gpu)), "NaN/Inf in the output: a tile read staging before its signal, or was skipped"
+    diff = C_gpu.astype(np.float64) - C_ref
+    rel = np.linalg.norm(diff) / max(np.linalg.norm(C_ref), 1e-300)
+    assert rel <= 1e-4, f"relative Frobenius error {rel}"
+    assert np.max(np.abs(diff)) <= 1e-3 * np.sqrt(K), f"max abs error {np.max(np.abs(diff))}"
+
+
+def check_bf16(C_bits: np.ndarray, C_f32: np.ndarray, C_ref: np.ndarray, K: int):
+    """bf16 output = RNE(fp32 accumulator) exactly; and within half a bf16 ulp (+ the fp32 bar) of the oracle."""
+    want = torch.from_numpy(C_f32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(C_bits, want)
+    got = bits_to_f64(C_bits)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(C_ref), 1e-30))) - 7)
+    assert np.all(np.abs(got - C_ref) <= 0.5 * ulp + 1e-3 * np.sqrt(K) * 2.0**-8 + 1e-30)
+
+
+@pytest.mark.parametrize("rank", [0, 1, 3])
+def test_tiny_random_arrival_order(rank):
+    inp = wl.make_ag_gemm(wl.AG_TINY)
+    ref = oracle.ag_gemm(inp.shards, inp.B_kn, rank)
+    run = AgGemmRun(inp, rank)
+    try:
+        rng = np.random.default_rng(1000 + rank)
+        order = [int(x) for x in rng.permutation([r for r in range(inp.shape.W) if r != rank])]
+        C = run.run(order).cpu().numpy()
+        check_f32(C, ref, inp.shape.K)
+    finally:
+        run.close()
+
+
+def test_tiny_bit_identical_over_all_arrival_orders_and_launch_orders():
+    inp = wl.make_ag_gemm(wl.AG_TINY)
+    run = AgGemmRun(inp, 0)
+    try:
+        base = None
+        for order in itertools.permutations([1, 2, 3]):
+            for consumer_first in (True, False):
+                C = run.run(list(order), consumer_first=consumer_first).cpu().numpy()
+                if base is None:
+                    base = C
+                    check_f32(C, oracle.ag_gemm(inp.shards, inp.B_kn, 0), inp.shape.K)
+                assert np.array_equal(C.view(np.uint32), base.view(np.uint32)), f"order {order} changed the bits"
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("tile", [0, 2])
+def test_integer_inputs_are_exact(tile):
+    # entries in {-2..2}: every partial sum is an integer below 2^24, so fp32 accumulation is exact
+    inp = wl.make_ag_gemm(wl.AG_RAGGED, a_dist=("int", 2), b_dist=("int", 2))
+    ref = oracle.ag_gemm(inp.shards, inp.B_kn, 1)
+    run = AgGemmRun(inp, 1)
+    try:
+        C = run.run(tile=tile).cpu().numpy()
+        assert np.array_equal(C.astype(np.float64), ref)
+    finally:
+        run.close()
+
+
+def test_identity_b_returns_gathered_a_bit_exactly():
+    sh = wl.AgGemmShape("eye", 9, 4, 64, 256, 256, out="f32")
+    inp = wl.make_ag_gemm(sh)
+    inp.B_kn = wl.f32_to_bf16_bits(np.eye(sh.K, dtype=np.float32))
+    run = AgGemmRun(inp, 2)
+    try:
+        C = run.run(out_dtype=agg.BF16)
+        assert np.array_equal(host_bits(C), np.concatenate(inp.shards))
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("tile", [0, 2])
+@pytest.mark.parametrize("chunks", [1, 4])
+def test_ragged_shape_f32_and_bf16(tile, chunks):
+    inp = wl.make_ag_gemm(wl.AG_RAGGED)         # M=600, N=328, K=320: ragged against every tile shape
+    ref = oracle.ag_gemm(inp.shards, inp.B_kn, 2)
+    run = AgGemmRun(inp, 2, chunks_per_shard=chunks)
+    try:
+        C32 = run.run(tile=tile).cpu().numpy()
+        check_f32(C32, ref, inp.shape.K)
+        C16 = host_bits(run.run(out_dtype=agg.BF16, tile=tile))
+        check_bf16(C16, C32, ref, inp.shape.K)
+    finally:
+        run.close()
+
+
+def test_shards_delivered_one_by_one_with_host_delays():
+    # the consumer is launched first and must block on each shard until the host lets it arrive
+    inp = wl.make_ag_gemm(wl.AG_TINY)
+    sh = inp.shape
+    ref = oracle.ag_gemm(inp.shards, inp.B_kn, 0)
+    run = AgGemmRun(inp, 0)
+    try:
+        run.poison()
+        agg.signal_reset(run.ctx)
+        C = torch.full((sh.M, sh.N), float("nan"), device="cuda", dtype=torch.float32)
+        torch.cuda.synchronize()
+        agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.cons)
+        agg.ag_producer_emulate(run.ctx, run.remote, [], agg.PRODUCER_KERNEL, 4, run.prod)      # local only
+        for r in (3, 1, 2):
+            time.sleep(0.02)
+            assert not run.cons.query(), "the consumer finished before every shard had arrived"
+            agg.ag_producer_emulate(run.ctx, run.remote, [r], agg.PRODUCER_KERNEL | agg.PRODUCER_SKIP_LOCAL, 4,
+                                    run.prod)
+        torch.cuda.synchronize()
+        assert agg.agg_status(run.ctx) == agg.OK
+        check_f32(C.cpu().numpy(), ref, sh.K)
+    finally:
+        run.close()
+
+
+def test_copy_engine_producer():
+    inp = wl.make_ag_gemm(wl.AG_TINY)
+    ref = oracle.ag_gemm(inp.shards, inp.B_kn, 1)
+    run = AgGemmRun(inp, 1, chunks_per_shard=2)
+    try:
+        for _ in range(2):          # twice: the second run must not see the first run's signals or data
+            C = run.run([0, 3, 2], mode=agg.PRODUCER_SDMA).cpu().numpy()
+            check_f32(C, ref, inp.shape.K)
+    finally:
+        run.close()
+
+
+def test_missing_shard_times_out_and_reports():
+    inp = wl.make_ag_gemm(wl.AG_TINY)
+    sh = inp.shape
+    run = AgGemmRun(inp, 0)
+    try:
+        run.ctx.set_wait_limit_us(20000)         # the host never delivers shard 2: the wait is bounded
+        agg.signal_reset(run.ctx)
+        C = torch.zeros((sh.M, sh.N), device="cuda", dtype=torch.float32)
+        agg.ag_producer_emulate(run.ctx, run.remote, [1, 3], agg.PRODUCER_KERNEL, 4, run.prod)
+        agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.cons)
+        torch.cuda.synchronize()
+        assert agg.agg_status(run.ctx) == agg.ERR_TIMEOUT
+        assert agg.agg_status(run.ctx) == agg.OK      # the record is cleared
+        # and the context still works afterwards
+        run.ctx.set_wait_limit_us(2000000)
+        C2 = run.run().cpu().numpy()
+        check_f32(C2, oracle.ag_gemm(inp.shards, inp.B_kn, 0), sh.K)
+    finally:
+        run.close()
+
+
+def test_argument_errors():
+    inp = wl.make_ag_gemm(wl.AG_TINY)
+    sh = inp.shape
+    run = AgGemmRun(inp, 0)
+    try:
+        C = torch.zeros((sh.M, sh.N), device="cuda", dtype=torch.float32)
+        def rc(**kw):
+            a = dict(M=sh.M, N=sh.N, K=sh.K, B=run.B_nk, ldb=sh.K, b_layout=agg.B_NK, Cout=C, ldc=sh.N, c_dtype=agg.F32)
+            a.update(kw)
+            with pytest.raises(agg.AggError) as e:
+                agg.ag_gemm(run.ctx, a["M"], a["N"], a["K"], a["B"], a["ldb"], a["b_layout"], a["Cout"], a["ldc"],
+                            a["c_dtype"], None)
+            return e.value.code
+        assert rc(K=sh.K - 16) == agg.ERR_UNSUPPORTED_SHAPE
+        assert rc(M=sh.M + 1) == agg.ERR_UNSUPPORTED_SHAPE
+        assert rc(M=sh.M + 4) == agg.ERR_UNSUPPORTED_SHAPE          # shard size no longer matches T
+        assert rc(B=None) == agg.ERR_INVALID_ARG
+        assert rc(B=run.B_nk.data_ptr() + 2) == agg.ERR_MISALIGNED
+        assert rc(ldb=sh.K + 4) == agg.ERR_MISALIGNED
+        assert rc(ldc=sh.N - 1) == agg.ERR_INVALID_ARG
+        assert rc(c_dtype=7) == agg.ERR_INVALID_ARG
+        agg.ag_gemm(run.ctx, 0, sh.N, sh.K, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, None)   # empty: no-op
+        with pytest.raises(agg.AggError):
+            agg.ag_producer_emulate(run.ctx, run.remote, [0], agg.PRODUCER_KERNEL, 0, None)    # own rank listed
+        with pytest.raises(agg.AggError):
+            agg.ag_producer_emulate(run.ctx, run.remote, [1, 1], agg.PRODUCER_KERNEL, 0, None)  # repeated
+        torch.cuda.synchronize()
+    finally:
+        run.close()
+
+
+# --------------------------------------------------------------------------- full-size workloads
+
+
+def _sample_rows(sh, n, seed):
+    rng = np.random.default_rng(seed)
+    rows = set(int(x) for x in rng.integers(0, sh.M, n))
+    # always include tile and shard edges
+    rows.update({0, sh.M - 1, sh.Ms - 1, sh.Ms, 255, 256, sh.M - sh.Ms})
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+@pytest.mark.parametrize("shape,n_orders", [(wl.AG_8B, 16), (wl.AG_70B, 4)])
+def test_full_size_sampled_rows_and_order_invariance(shape, n_orders):
+    inp = wl.make_ag_gemm(shape)
+    rank = 3
+    rows = _sample_rows(shape, 48, shape.cfg)
+    ref = oracle.ag_gemm(inp.shards, inp.B_kn, rank, rows=rows)
+    run = AgGemmRun(inp, rank, chunks_per_shard=4)
+    try:
+        C32 = run.run(consumer_first=False).cpu().numpy()
+        check_f32(C32[rows], ref, shape.K)
+        assert np.all(np.isfinite(C32))
+        orders = wl.arrival_orders(shape.W, rank, limit=n_orders, seed=shape.cfg)
+        base16 = None
+        for order in orders:
+            C16 = host_bits(run.run(order, out_dtype=agg.BF16, consumer_first=False))
+            if base16 is None:
+                base16 = C16
+                check_bf16(C16[rows], C32[rows], ref, shape.K)
+                # whole-matrix property: bf16 output is the rounded fp32 output everywhere
+                want = torch.from_numpy(C32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+                assert np.array_equal(C16, want)
+            else:
+                assert np.array_equal(C16, base16), f"arrival order {order} changed the output bits"
+    finally:
+        run.close()
