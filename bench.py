@@ -1,0 +1,198 @@
+"""Benchmark of the AllGather-GEMM hot path on one MI355X.
+
+One step = signal_reset, the emulated producer on the producer stream and the signal-gated GEMM on the
+consumer stream (the whole fused AG+GEMM of the 70B-MLP-shaped workload).  Prints ONE JSON line.
+Inputs are synthetic, seeded, and resident in HBM before the timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak (published)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="ag_gemm_70b_mlp")
+    ap.add_argument("--tile", type=int, default=-1)
+    ap.add_argument("--chunks", type=int, default=4, help="signals per shard")
+    ap.add_argument("--producer-wgs", type=int, default=0)
+    ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of C the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the reducer / serial / copy-only timings")
+    ap.add_argument("--shape", default="", help="profiling aid: W,Ms,K,N of an ad-hoc AllGather-GEMM shape")
+    ap.add_argument("--only-gemm", action="store_true",
+                    help="profiling aid: deliver the shards once, then time the GEMM alone (prints a short line)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (peers are emulated on the same GPU); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2504_19442_amd as agg
+    import workloads as wl
+    from gpu_util import AgGemmRun
+
+    if args.shape:
+        W_, Ms_, K_, N_ = (int(x) for x in args.shape.split(","))
+        shape = wl.AgGemmShape("adhoc_" + args.shape.replace(",", "x"), 99, W_, Ms_, K_, N_)
+    else:
+        shape = wl.AG_SHAPES[args.workload]
+    inp = wl.make_ag_gemm(shape)
+    rank = 0
+    run = AgGemmRun(inp, rank, chunks_per_shard=args.chunks)
+    ctx = run.ctx
+    ctx.set_tile_config(args.tile)
+    M, N, K = shape.M, shape.N, shape.K
+    C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+    prod, cons = run.prod, run.cons
+    ev_cons_done = torch.cuda.Event()
+
+    def step_fused(ev_pairs=None):
+        agg.signal_reset(ctx)
+        prod.wait_event(ev_cons_done)          # T is shared: the next arrival waits for the last consumer
+        agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, prod)
+        if ev_pairs is not None:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(cons)
+        agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
+        if ev_pairs is not None:
+            e1.record(cons)
+            ev_pairs.append((e0, e1))
+        ev_cons_done.record(cons)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    if args.only_gemm:
+        agg.signal_reset(ctx)
+        agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, prod)
+        torch.cuda.synchronize()
+        t = timed(lambda: agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons), args.steps,
+                  args.warmup)
+        assert agg.agg_status(ctx) == agg.OK
+        print(json.dumps({"only_gemm_ms": round(t * 1e3, 4), "tflops": round(shape.flops / t / 1e12, 1),
+                          "workload": shape.name, "tile_config": args.tile}), flush=True)
+        run.close()
+        return 0
+
+    ev_cons_done.record(cons)
+    # ---- the headline: fused step
+    for _ in range(args.warmup):
+        step_fused()
+    torch.cuda.synchronize()
+    pairs = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_fused(pairs)
+    torch.cuda.synchronize()
+    t_fused = (time.perf_counter() - t0) / args.steps
+    assert agg.agg_status(ctx) == agg.OK, "a wait timed out during the bench"
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+    flops = shape.flops
+    tflops = flops / t_fused / 1e12
+
+    out = {
+        "metric": "AG-GEMM TFLOP/s (fraction of bf16 MFMA peak) + overlap efficiency vs serial",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(t_fused * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": shape.name, "W": shape.W, "rank": rank, "M": M, "N": N, "K": K,
+                   "signals_per_shard": args.chunks, "tile_config": args.tile, "out": "bf16",
+                   "producer": "copy kernel on the producer stream"},
+        "fraction_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "roofline": {"bound": "mfma", "achieved": round(flops / (kern_ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(flops / (kern_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None, "kernel": "gemm_kernel (signal-gated, fused run)",
+                     "kernel_ms": round(kern_ms, 4)},
+    }
+
+    if not args.no_extras:
+        # GEMM alone (signals already set for this epoch), copy alone, serial copy-then-GEMM on one stream
+        def step_gemm():
+            agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
+
+        def step_copy():
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, prod)
+
+        def step_serial():
+            agg.signal_reset(ctx)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, cons)
+            agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
+
+        n2 = max(10, args.steps // 2)
+        t_gemm = timed(step_gemm, n2, 3)
+        t_copy = timed(step_copy, n2, 3)
+        t_serial = timed(step_serial, n2, 3)
+        assert agg.agg_status(ctx) == agg.OK
+        out["overlap"] = {
+            "t_fused_ms": round(t_fused * 1e3, 4), "t_gemm_ms": round(t_gemm * 1e3, 4),
+            "t_copy_ms": round(t_copy * 1e3, 4), "t_serial_ms": round(t_serial * 1e3, 4),
+            "overlap_efficiency": round(t_serial / t_fused, 4),
+            "hidden_fraction": round((t_serial - t_fused) / t_copy, 4),
+            "gemm_alone_tflops": round(flops / t_gemm / 1e12, 2),
+            "fused_over_gemm": round(t_fused / t_gemm, 4),
+        }
+        # the reducer of GEMM+ReduceScatter at its full size (all signals set: pure streaming reduction)
+        rs = wl.RS_FULL
+        slots = [torch.randn((rs.Ms, rs.N), device="cuda", dtype=torch.float32) for _ in range(rs.W)]
+        R = torch.empty((rs.Ms, rs.N), device="cuda", dtype=torch.float32)
+        rctx = agg.symm_alloc(rs.W, 0, 16, rs.W)
+        rp, rc_ = rctx.streams()
+        rcs = torch.cuda.ExternalStream(rc_)
+        agg.signal_reset(rctx)
+        for w in range(rs.W):
+            agg.signal_set(rctx, w, rc_)
+
+        def step_reduce():
+            agg.rs_reduce(rctx, rs.Ms, rs.N, slots, R, rs.N, agg.F32, 0, rc_)
+
+        t_red = timed(step_reduce, 50, 5)
+        assert agg.agg_status(rctx) == agg.OK
+        rctx.free()
+        out["reducer"] = {"workload": rs.name, "bytes": rs.reducer_bytes, "ms": round(t_red * 1e3, 4),
+                          "achieved_GBps": round(rs.reducer_bytes / t_red / 1e9, 1),
+                          "frac_of_hbm_peak": round(rs.reducer_bytes / t_red / 1e9 / PEAK_HBM_GBPS, 4)}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of rows of the same workload
+    if args.cpu_rows > 0:
+        import oracle
+        rows = np.arange(0, M, max(1, M // args.cpu_rows), dtype=np.int64)[: args.cpu_rows]
+        t0 = time.perf_counter()
+        ref = oracle.ag_gemm(inp.shards, inp.B_kn, rank, rows=rows)
+        dt = time.perf_counter() - t0
+        got = C[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
+        ok = bool(np.all(np.abs(got - ref) <= 0.5 * ulp + 1e-3 * np.sqrt(K) * 2.0**-8))
+        out["cpu_baseline"] = {"value": round(2.0 * len(rows) * N * K / dt / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"{len(rows)} evenly spaced rows of C (all {N} columns), {dt:.2f} s",
+                               "gpu_matches_oracle_on_sample": ok}
+    run.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -169,8 +169,7 @@ int ag_moe_gemm(agg_ctx* ctx, int Ttok, int topk, int E, int N, int K,
                 int32_t* sorted_token, int32_t* sorted_expert_offsets,
                 void* Y, int ldy, int y_dtype, void* stream);
 
-/* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 256x256,
- * 2 = 128x128.  A tuning knob (Section 3.8); every shape gives the same result up to fp32 summation order. */
+/* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 128x128.  A tuning knob (Section 3.8); every shape gives the same result up to fp32 summation order. */
 int agg_set_tile_config(agg_ctx* ctx, int tile_config);
 
 const char* agg_strerror(int code);

@@ -33,7 +33,8 @@ EXPORTS = [
 
 
 def lib_path() -> str:
-    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libagg.so")
+    """The built library; AGG_LIB_PATH names another build of the same sources (kernel experiments)."""
+    return os.environ.get("AGG_LIB_PATH") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libagg.so")
 
 
 _LIB = None

@@ -14,8 +14,36 @@ LIB = os.path.join(HERE, "libagg.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions on the test machines.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# -amdgpu-spill-vgpr-to-agpr=0: the GEMM kernel keeps its accumulators in accumulator registers the compiler
+# does not know about, so the compiler must never park values of its own there (check_agprs verifies it).
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-inline-asm",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"]
+
+
+def check_agprs(extra_flags=()) -> None:
+    """Compile the GEMM kernel to assembly and fail if the compiler itself touches an accumulator register
+    (any a<N> outside the inline-asm blocks), or if a kernel spills to scratch."""
+    import re
+    src = os.path.join(CSRC, "gemm_kernel.hip")
+    r = subprocess.run([HIPCC, *FLAGS, *extra_flags, "--cuda-device-only", "-S", src, "-o", "-"],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(r.stderr)
+    in_asm = False
+    pat = re.compile(r"(?<![A-Za-z0-9_.])a(\[\d+(:\d+)?\]|\d+\b)")
+    for n, line in enumerate(r.stdout.splitlines(), 1):
+        t = line.strip()
+        if t.startswith(";;#ASMSTART"):
+            in_asm = True
+        elif t.startswith(";;#ASMEND"):
+            in_asm = False
+        elif not in_asm and not t.startswith(";") and not t.startswith("."):
+            code = t.split(";")[0]
+            if pat.search(code):
+                raise RuntimeError(f"compiler-allocated accumulator register in gemm_kernel (asm line {n}): {t}")
+        if t.startswith("; ScratchSize:") and t.split(":")[1].strip() != "0":
+            raise RuntimeError(f"gemm_kernel spills to scratch: {t}")
 
 
 def _compile(src: str) -> str:
@@ -33,6 +61,23 @@ def _compile(src: str) -> str:
     return obj
 
 
+def build_variant(out_path: str, extra_flags: list) -> str:
+    """Build the same sources with extra compiler flags into out_path (kernel experiments; never the product)."""
+    import tempfile
+    check_agprs(extra_flags)
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    with tempfile.TemporaryDirectory() as tmp:
+        objs = []
+        for src in srcs:
+            obj = os.path.join(tmp, os.path.basename(src) + ".o")
+            r = subprocess.run([HIPCC, *FLAGS, *extra_flags, "-c", src, "-o", obj], capture_output=True, text=True)
+            if r.returncode != 0:
+                raise RuntimeError(r.stderr)
+            objs.append(obj)
+        subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out_path], check=True)
+    return out_path
+
+
 def build(force: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
     if force:
@@ -43,6 +88,7 @@ def build(force: bool = True) -> str:
             objs = list(ex.map(_compile, srcs))
     finally:
         os.environ.pop("AGG_FORCE_BUILD", None)
+    check_agprs()
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB + ".tmp"], check=True)
     os.replace(LIB + ".tmp", LIB)
     return LIB

@@ -21,6 +21,7 @@ struct GemmParams {
     long long lda, ldb, ldc, ldc_own;
     int M, N, K;
     int c_is_f32;
+    int c_vec_ok;         // C (and C_own) and their leading dimensions allow 16-byte row-chunk stores
     // tile schedule (Section 3.7: rank-rotated order, local shard first)
     int tiles_m, tiles_n;
     int panel_m;          // m-tiles per panel (a panel = the tiles of one shard step)
@@ -40,14 +41,13 @@ struct GemmParams {
     int* done_flag;
 };
 
-enum TileConfig { TILE_256x224 = 0, TILE_256x256 = 1, TILE_128x128 = 2, TILE_CONFIGS };
+enum TileConfig { TILE_256x224 = 0, TILE_128x128 = 1, TILE_CONFIGS };
 
 struct TileShape { int bm, bn; };
 inline TileShape tile_shape(int cfg)
 {
     switch (cfg) {
         case TILE_256x224: return {256, 224};
-        case TILE_256x256: return {256, 256};
         default: return {128, 128};
     }
 }

@@ -276,6 +276,7 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     p.N = N;
     p.K = K;
     p.c_is_f32 = c_dtype == AGG_F32;
+    p.c_vec_ok = aligned16(C) && ((long long)ldc * (p.c_is_f32 ? 4 : 2)) % 16 == 0;
     const int cfg = choose_tile(c, M, N);
     fill_schedule(p, cfg, Ms, c->rank * Ms);
     p.flags = c->signals;
@@ -357,6 +358,7 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
     p.N = N;
     p.K = Kl;
     p.c_is_f32 = 1;
+    p.c_vec_ok = aligned16(slots[c->rank]) && (!P_other || aligned16(P_other)) && N % 4 == 0;
     p.epoch = c->epoch;
     p.err = c->err;
     p.wait_ticks = wait_ticks(c);

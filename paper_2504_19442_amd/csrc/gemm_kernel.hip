@@ -9,23 +9,77 @@
 // pair of Section 2.2.
 //
 // Main loop: K is cut into steps of 32.  A and B tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4, 16 bytes per lane) through a ring of NS stages, so NS-1 steps of loads are
+// (buffer_load_dwordx4 ... lds, 16 bytes per lane) through a ring of NS stages, so NS-1 steps of loads are
 // in flight while one is computed.  Rows are 64 bytes in LDS; the 16-byte chunk c of row r sits in slot
 // c ^ ((r >> 2) & 3), which makes the ds_read_b128 operand fetches bank-conflict free.  Each wave owns
-// BM/4 rows and all BN columns of the tile and feeds v_mfma_f32_32x32x16_bf16 from two register sets
-// of fragments that are refilled one half-step ahead of their use.  One workgroup barrier per step.
+// BM/4 rows and all BN columns of the tile and feeds v_mfma_f32_32x32x16_bf16 from register sets of
+// fragments that are refilled one half-step ahead of their use.  One workgroup barrier per step.  The
+// fragment reads and global->LDS loads of a step are dealt out one per MFMA (a wave issues in order and a
+// memory instruction is slow to issue, so bunches of them between two MFMAs starve the matrix pipe).
+// The MFMA computes the transposed block (B fragment as first operand), so that a lane ends up holding
+// four consecutive columns of one output row; the epilogue stages each wave's rows through LDS and
+// stores them to C as whole 16-byte row chunks.
+//
+// Registers: the fp32 accumulators live in accumulator registers a0..a(MB*NB*16-1) that only the inline
+// asm of this file touches (MFMA, zeroing, read-out); the compiler allocates the ordinary registers and is
+// capped so that the kernel takes 448 of the 512 registers of a SIMD.  The 64 left over are what lets one
+// wave of a small kernel (the producer's copy waves, the reducer) run beside a consumer wave on every
+// SIMD: communication and computation share all CUs instead of splitting them (Section 3.8).
 #include "agg_internal.h"
+
+#include <type_traits>
+#include <utility>
 
 namespace agg {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
-#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// Raw buffer descriptor over `bytes` bytes at p: loads whose per-lane offset is >= bytes return zero, which
+// is how rows past the edge of A or B are masked.  0x00020000 = 32-bit data format, no swizzle (gfx9 family).
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
 
 // s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]).
 __host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | ((n >> 4) << 14); }
+
+// compile-time loop: f(std::integral_constant<int, I>) for I in [0, N)
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// ---- accumulator registers, touched only here.  Block b is a[16b : 16b+15].
+template <int BLK>
+__device__ __forceinline__ void mfma_acc(const bf16x8& a, const bf16x8& b)
+{
+#ifdef AGG_EXP_NO_MFMA
+    asm volatile("; no mfma %2 %3" ::"v"(a), "v"(b), "n"(BLK * 16), "n"(BLK * 16 + 15));
+#else
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3]" ::"v"(a), "v"(b), "n"(BLK * 16), "n"(BLK * 16 + 15));
+#endif
+}
+template <int R>
+__device__ __forceinline__ void acc_zero()
+{
+    asm volatile("v_accvgpr_write_b32 a[%0], 0" ::"n"(R));
+}
+template <int R>
+__device__ __forceinline__ float acc_read()
+{
+    float x;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(x) : "n"(R));
+    return x;
+}
 
 constexpr int BK = 32;                 // bf16 per K-step
 constexpr int ROW_BYTES = BK * 2;      // 64-byte rows in LDS
@@ -36,6 +90,7 @@ struct Cfg {
     static constexpr int TM = BM / 4;            // rows per wave
     static constexpr int MB = TM / 32;           // 32x32 blocks per wave, M direction
     static constexpr int NB = BN / 32;           // and N direction
+    static constexpr int ACC = MB * NB * 16;     // accumulator registers per lane
     static constexpr int A_UNITS = BM / UNIT_ROWS;
     static constexpr int B_UNITS = BN / UNIT_ROWS;
     static constexpr int UNITS = A_UNITS + B_UNITS;
@@ -49,14 +104,39 @@ struct Cfg {
     static_assert(REM == 0 || REM == 2, "unsupported unit count");
     static_assert(NS >= 3 && NS % 2 == 0, "ring needs at least 3 stages, and an even count for the fragment-set rotation");
     static_assert((NS - 2) * L <= 63, "vmcnt range");
+    static_assert(ACC == 64 || ACC == 128 || ACC == 224 || ACC == 256, "add a reservation line for this accumulator count");
+    // MFMA slots of one K-step: [0, SLOTS_A) before the barrier, then the rest of half-step 0, then half-step 1
+    // (slots [SLOTS/2, SLOTS)).  A wave issues in order, and a memory instruction takes long enough to issue
+    // that more than one or two of them between two MFMAs leaves the matrix pipe idle; so every slot gets at
+    // most QUOTA memory instructions.  First half of the step: the F = MB+NB fragment reads of half-step 1,
+    // then L1 of the step's global->LDS loads; second half: the F fragment reads of the next step's
+    // half-step 0, then the remaining loads.
+    static constexpr int H = NB / 2;
+    static constexpr int SLOTS = 2 * MB * NB;
+    static constexpr int SLOTS_A = MB * H;
+    static constexpr int F = MB + NB;
+    static constexpr int QUOTA = (2 * F + L + SLOTS - 1) / SLOTS;
+    static constexpr int CAP = (SLOTS / 2) * QUOTA;              // memory instructions per half
+    static constexpr int L1 = (L < CAP - F) ? L : CAP - F;       // loads issued in the first half
+    static_assert(CAP >= F && F + (L - L1) <= CAP, "memory instructions do not fit the slots");
+    static_assert(F / QUOTA >= SLOTS_A, "the first load of a step must come after the barrier");
+    // epilogue staging: each wave stages 32 rows x BN columns at a time
+    static constexpr int PITCH_BF16 = BN * 2 + 16;
+    static constexpr int PITCH_F32 = BN * 4 + 16;
+    static_assert(4 * 32 * PITCH_F32 <= LDS_BYTES, "epilogue staging does not fit in the ring");
 };
 
 template <int BM, int BN, int NS>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gemm_kernel(const GemmParams p)
 {
+#if defined(__HIP_DEVICE_COMPILE__)    // the body names gfx950 registers; the host pass only needs the launch stub
     using C_ = Cfg<BM, BN, NS>;
     constexpr int MB = C_::MB, NB = C_::NB, L = C_::L, FULL = C_::FULL, TM = C_::TM;
-    constexpr int H = NB / 2;            // column blocks of half-step 0 issued before the barrier
+    // naming the last accumulator register makes the compiler reserve a0..a(ACC-1) for this kernel
+    if constexpr (C_::ACC == 256) asm volatile("; accumulators a0..a255" ::: "a255");
+    else if constexpr (C_::ACC == 224) asm volatile("; accumulators a0..a223" ::: "a223");
+    else if constexpr (C_::ACC == 128) asm volatile("; accumulators a0..a127" ::: "a127");
+    else asm volatile("; accumulators a0..a63" ::: "a63");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     const int tid = threadIdx.x;
@@ -117,151 +197,243 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p)
                 }
             }
             if (gave_up) __hip_atomic_store(p.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#ifndef AGG_EXP_NO_ACQ
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
             if (__syncthreads_or(gave_up)) return;   // the launch drains; agg_status reports the time-out
         }
 
-        // ---- per-tile load offsets (bytes from the tile's A / B origin; rows past the edge are clamped)
-        const unsigned char* a_base = (const unsigned char*)(p.A + (long long)m0 * p.lda);
-        const unsigned char* b_base = (const unsigned char*)(p.B + (long long)n0 * p.ldb);
-        const int m_last = p.M - 1 - m0, n_last = p.N - 1 - n0;
+        // ---- per-tile buffer descriptors and per-lane load offsets (bytes from the tile's A / B origin);
+        // rows past the edge of the matrix fall outside the descriptor and load as zero
+        const __amdgpu_buffer_rsrc_t a_rsrc =
+            make_rsrc(p.A + (long long)m0 * p.lda, (unsigned)(min(BM, p.M - m0) * (int)p.lda * 2));
+        const __amdgpu_buffer_rsrc_t b_rsrc =
+            make_rsrc(p.B + (long long)n0 * p.ldb, (unsigned)(min(BN, p.N - n0) * (int)p.ldb * 2));
         unsigned ld_off[L];
 #pragma unroll
         for (int i = 0; i < L; ++i) {
             const int u = (i < FULL) ? wave + 4 * i : 4 * FULL + (wave >> 1);
-            if (u < C_::A_UNITS) {
-                const int r = min(u * UNIT_ROWS + ld_row, m_last);
-                ld_off[i] = (unsigned)(r * (int)p.lda * 2 + ld_chunk * 16);
-            } else {
-                const int r = min((u - C_::A_UNITS) * UNIT_ROWS + ld_row, n_last);
-                ld_off[i] = (unsigned)(r * (int)p.ldb * 2 + ld_chunk * 16);
-            }
+            if (u < C_::A_UNITS)
+                ld_off[i] = (unsigned)((u * UNIT_ROWS + ld_row) * (int)p.lda * 2 + ld_chunk * 16);
+            else
+                ld_off[i] = (unsigned)(((u - C_::A_UNITS) * UNIT_ROWS + ld_row) * (int)p.ldb * 2 + ld_chunk * 16);
         }
 
-        auto load_stage = [&](int st, int kt) {
-            const unsigned char* ak = a_base + (long long)kt * ROW_BYTES;
-            const unsigned char* bk = b_base + (long long)kt * ROW_BYTES;
-#pragma unroll
-            for (int i = 0; i < L; ++i) {
-                const int u = (i < FULL) ? wave + 4 * i : 4 * FULL + (wave >> 1);
-                // whether unit i of this wave is an A or a B unit is the same for all four waves
-                const bool is_a = ((i < FULL) ? 4 * i : 4 * FULL) < C_::A_UNITS;
-                const unsigned char* src = (is_a ? ak : bk) + ld_off[i];
-                unsigned char* dst = lds + st * C_::STAGE_BYTES + u * 1024;
-                __builtin_amdgcn_global_load_lds(GLOBAL_PTR(src), LDS_PTR(dst), 16, 0, 0);
+        // one global->LDS load (unit i of this wave) of K-step kt into stage st
+        auto load_unit = [&](int i, int st, int kt) {
+            const int u = (i < FULL) ? wave + 4 * i : 4 * FULL + (wave >> 1);
+            // whether unit i of this wave is an A or a B unit is the same for all four waves
+            const bool is_a = ((i < FULL) ? 4 * i : 4 * FULL) < C_::A_UNITS;
+#ifdef AGG_EXP_SAME_M0
+            unsigned char* dst = lds + st * C_::STAGE_BYTES + (u & 3) * 1024;
+#else
+            unsigned char* dst = lds + st * C_::STAGE_BYTES + u * 1024;
+#endif
+#if defined(AGG_EXP_MB1)
+            // microbenchmark-like addressing, step 1: one descriptor, private rows per wave, 2 KiB window
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, LDS_PTR(dst), 16,
+                                                     (unsigned)((wave * 64 + i * 16 + ld_row) * 16384 + ld_chunk * 16) % (3u << 20),
+                                                     (kt & 31) * ROW_BYTES, 0, 0);
+#elif defined(AGG_EXP_MB2)
+            // step 2: real descriptors and offsets, but the K offset cycles inside a 2 KiB window
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
+                                                     (kt & 31) * ROW_BYTES, 0, 0);
+#elif defined(AGG_EXP_MB3)
+            // step 3: real K offsets, one descriptor
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, LDS_PTR(dst), 16,
+                                                     (unsigned)((wave * 64 + i * 16 + ld_row) * 16384 + ld_chunk * 16) % (3u << 20),
+                                                     kt * ROW_BYTES, 0, 0);
+#elif defined(AGG_EXP_MB4)
+            // real offsets, one descriptor
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, LDS_PTR(dst), 16, ld_off[i], kt * ROW_BYTES, 0, 0);
+#elif defined(AGG_EXP_MB5)
+            // two descriptors, wave-private rows
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16,
+                                                     (unsigned)((wave * 64 + i * 16 + ld_row) * 16384 + ld_chunk * 16) % (3u << 20),
+                                                     kt * ROW_BYTES, 0, 0);
+#elif defined(AGG_EXP_MB6)
+            // two descriptors, real row ranges, rows contiguous per wave
+            {
+                const int unit = is_a ? wave * 4 + i : min(wave * 4 + (i - 4), C_::B_UNITS - 1);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16,
+                                                         (unsigned)((unit * 16 + ld_row) * 16384 + ld_chunk * 16),
+                                                         kt * ROW_BYTES, 0, 0);
             }
+#elif defined(AGG_EXP_MB7)
+            // real pattern but B rows taken from the A tile region +256 rows (distinct lines, A descriptor)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, LDS_PTR(dst), 16, ld_off[i] + (is_a ? 0u : 0u),
+                                                     kt * ROW_BYTES + (is_a ? 0 : 8192 * 2 * 0), 0, 0);
+#elif defined(AGG_EXP_SAME_K)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
+                                                     (kt & 1) * ROW_BYTES, 0, 0);
+#elif defined(AGG_EXP_LOAD_VGPR)
+            typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4_;
+            u32x4_ v_ = __builtin_amdgcn_raw_buffer_load_b128(is_a ? a_rsrc : b_rsrc, ld_off[i], kt * ROW_BYTES, 0);
+            asm volatile("" ::"v"(v_));
+            (void)dst;
+#else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
+                                                     kt * ROW_BYTES, 0, 0);
+#endif
         };
 
-        // four fragment sets: set 2*(kt&1) + s holds half-step s of step kt, so a set is refilled a whole
-        // half-step before it is used and never while MFMAs that read it are still to be issued
-        bf16x8 fa[4][MB], fb[4][NB];
-        auto read_frags = [&](int st, int s, int set) {
-            const unsigned char* sa = lds + st * C_::STAGE_BYTES + wave * TM * ROW_BYTES + fr_off[s];
-            const unsigned char* sb = lds + st * C_::STAGE_BYTES + BM * ROW_BYTES + fr_off[s];
-#pragma unroll
-            for (int i = 0; i < MB; ++i) fa[set][i] = *(const bf16x8*)(sa + i * 32 * ROW_BYTES);
-#pragma unroll
-            for (int j = 0; j < NB; ++j) fb[set][j] = *(const bf16x8*)(sb + j * 32 * ROW_BYTES);
+        // three fragment sets: sets 0 and 1 alternate for half-step 0 (the next step's is fetched while the
+        // current one is still being used), set 2 serves half-step 1.  Fragment f < MB is the A fragment of
+        // row block f, fragment MB + j the B fragment of column block j.
+        bf16x8 fr[3][MB + NB];
+        auto read_frag = [&](int f, int st, int s, int set) {
+            const unsigned char* src = lds + st * C_::STAGE_BYTES + fr_off[s] +
+                                       (f < MB ? (wave * TM + f * 32) * ROW_BYTES : (BM + (f - MB) * 32) * ROW_BYTES);
+            fr[set][f] = *(const bf16x8*)src;
         };
 
-        f32x16 acc[MB][NB];
-#pragma unroll
-        for (int i = 0; i < MB; ++i)
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-        auto mma = [&](int set, int j_lo, int j_hi) {
-#pragma unroll
-            for (int j = j_lo; j < j_hi; ++j)
-#pragma unroll
-                for (int i = 0; i < MB; ++i)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
-        };
+#ifdef AGG_EXP_TIMING
+        const long long tt0 = __builtin_readcyclecounter();
+#endif
+        static_for<C_::ACC>([&](auto r) { acc_zero<decltype(r)::value>(); });
 
         // ---- prologue: NS-1 stages in flight (steps past the end re-load the last step: harmless, and it
         // keeps the number of outstanding loads per wave the same on every path)
 #pragma unroll
-        for (int i = 0; i < NS - 1; ++i) load_stage(i, min(i, KT - 1));
+        for (int st = 0; st < NS - 1; ++st)
+#pragma unroll
+            for (int i = 0; i < L; ++i) load_unit(i, st, min(st, KT - 1));
         __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * L));
         __builtin_amdgcn_s_barrier();
-        read_frags(0, 0, 0);
+#pragma unroll
+        for (int f = 0; f < MB + NB; ++f) read_frag(f, 0, 0, 0);
 
-        // ---- main loop, unrolled over the ring so that stage and set indices are constants; the only
-        // branches are the loop exits, so the body stays one straight line for the scheduler
+        // experiment switches (never defined in the product build): drop work from the main loop to see what it costs
+#ifdef AGG_EXP_NO_LDSREAD
+#define LOOP_READ_FRAG(...) ((void)0)
+#else
+#define LOOP_READ_FRAG(...) read_frag(__VA_ARGS__)
+#endif
+#ifdef AGG_EXP_NO_GLOAD
+#define LOOP_LOAD_UNIT(...) ((void)0)
+#else
+#define LOOP_LOAD_UNIT(...) load_unit(__VA_ARGS__)
+#endif
+        // ---- main loop, unrolled over the ring so that stage and set indices are constants.  The MFMAs are
+        // volatile asm, so memory operations keep their place between them: the interleaving below is the
+        // schedule.  Slot q of a half-step works on column block q / MB, row block q % MB; the B fragment is
+        // the first MFMA operand, so accumulator block (i, j) holds the transposed 32x32 block.
+#ifdef AGG_EXP_TIMING
+        const long long tt1 = __builtin_readcyclecounter();
+#endif
         for (int kt0 = 0;; kt0 += NS) {
-#pragma unroll
-            for (int st = 0; st < NS; ++st) {
+            bool done = false;
+            static_for<NS>([&](auto st_c) {
+                constexpr int st = decltype(st_c)::value;
+                constexpr int cur = st & 1, nxt = (st + 1) & 1;
+                if (done) return;
                 const int kt = kt0 + st;
-                const int cur = 2 * (st & 1), nxt = 2 * ((st + 1) & 1);
-                // (A) first part of half-step 0 on the matrix pipe while the fragments of half-step 1 leave LDS
-                mma(cur, 0, H);
-                read_frags(st, 1, cur + 1);
-#pragma unroll
-                for (int q = 0; q < MB * H; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                // stage kt+1 has landed for this wave once at most the younger stages are outstanding
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * L));
-                __builtin_amdgcn_s_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-                // (B) every wave is past its reads of stage kt-1: refill it with step kt+NS-1, fetch the next
-                // step's first fragments (early, so they are back before part C ends), rest of half-step 0
-                mma(cur, H, NB);
-                read_frags((st + 1) % NS, 0, nxt);
-                load_stage((st + NS - 1) % NS, min(kt + NS - 1, KT - 1));
-#pragma unroll
-                for (int q = 0; q < MB * (NB - H); ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
-                    __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);   // address arithmetic
-                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global->LDS load
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                // (C) half-step 1
-                mma(cur + 1, 0, NB);
-                __builtin_amdgcn_sched_barrier(0);
-                if (kt + 1 >= KT) goto k_done;
-            }
-        }
-    k_done:
-
-        // ---- epilogue: accumulators to C.  32x32 block layout: lane l holds column l%32 and, in
-        // register v, row 8*(v/4) + 4*(l/32) + v%4.
-        {
-            const int col = n0 + (lane & 31);
-            const int row_w = m0 + wave * TM + 4 * (lane >> 5);
-#pragma unroll
-            for (int i = 0; i < MB; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row_w + i * 32 + 8 * (v >> 2) + (v & 3);
-                    if (row < p.M) {
-                        void* cbase = p.C;
-                        long long ldc = p.ldc;
-                        long long rr = row;
-                        if (p.C_own && row >= p.own_lo && row < p.own_hi) {
-                            cbase = p.C_own;
-                            ldc = p.ldc_own;
-                            rr = row - p.own_lo;
+                const int kt_load = min(kt + NS - 1, KT - 1);
+                // the memory instructions that follow the MFMA of slot `slot`
+                auto mem_after = [&](auto slot_c) {
+                    constexpr int slot = decltype(slot_c)::value;
+                    constexpr bool second = slot >= C_::SLOTS / 2;
+                    static_for<C_::QUOTA>([&](auto k_c) {
+                        constexpr int o = (slot % (C_::SLOTS / 2)) * C_::QUOTA + decltype(k_c)::value;
+                        if constexpr (o < C_::F) {
+                            // fragment reads: half-step 1 of this step, or half-step 0 of the next step
+                            if constexpr (!second) LOOP_READ_FRAG(o, st, 1, 2);
+                            else LOOP_READ_FRAG(o, (st + 1) % NS, 0, nxt);
+                        } else {
+                            // global->LDS loads of step kt+NS-1 into the stage every wave finished reading
+                            // before the barrier of this step
+                            constexpr int i = (second ? C_::L1 : 0) + o - C_::F;
+                            if constexpr (i < (second ? L : C_::L1)) LOOP_LOAD_UNIT(i, (st + NS - 1) % NS, kt_load);
                         }
-                        if (cbase) {
-#pragma unroll
-                            for (int j = 0; j < NB; ++j) {
-                                const int c = col + j * 32;
-                                if (c < p.N) {
-                                    if (p.c_is_f32)
-                                        ((float*)cbase)[rr * ldc + c] = acc[i][j][v];
-                                    else
-                                        ((__bf16*)cbase)[rr * ldc + c] = (__bf16)acc[i][j][v];
-                                }
-                            }
-                        }
+                    });
+                };
+                static_for<C_::SLOTS>([&](auto q_c) {
+                    constexpr int slot = decltype(q_c)::value;
+                    constexpr int set = slot < C_::SLOTS / 2 ? cur : 2;
+                    constexpr int q = slot % (C_::SLOTS / 2);       // column block q / MB, row block q % MB
+                    mfma_acc<(q % MB) * NB + q / MB>(fr[set][MB + q / MB], fr[set][q % MB]);
+                    mem_after(q_c);
+                    if constexpr (slot == C_::SLOTS_A - 1) {
+#ifndef AGG_EXP_NO_BARRIER
+                        // stage kt+1 has landed for this wave once at most the younger stages are outstanding;
+                        // after the barrier it has landed for all waves, and all waves are done with stage kt-1
+                        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * L));
+                        __builtin_amdgcn_s_barrier();
+#endif
                     }
+                });
+                if (kt + 1 >= KT) done = true;
+            });
+            if (done) break;
+        }
+
+        // ---- epilogue.  Accumulator block (i, j) is the transposed block: lane l holds output row
+        // i*32 + l%32 and, in register v, column j*32 + 8*(v/4) + 4*(l/32) + v%4 -- four consecutive columns per
+        // group of four registers.
+#ifdef AGG_EXP_TIMING
+        const long long tt2 = __builtin_readcyclecounter();
+#endif
+        asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7");     // the last MFMAs retire before the read-out
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));              // the last (redundant) loads have landed in LDS
+        __syncthreads();                                       // and every wave is done with the ring
+        {
+            int lane_e = lane;
+            asm volatile("" : "+v"(lane_e));     // keeps the address arithmetic below inside the tile loop
+            const int row_w = m0 + wave * TM;    // first output row of this wave
+            const bool fast = p.c_vec_ok && n0 + BN <= p.N;
+            // where a row of the output goes: C, or (GEMM-RS) this rank's own slot; nullptr = not stored
+            auto row_ptr = [&](int row, int esz) -> char* {
+                if (row >= p.M) return nullptr;
+                if (p.C_own && row >= p.own_lo && row < p.own_hi)
+                    return (char*)p.C_own + ((long long)(row - p.own_lo) * p.ldc_own + n0) * esz;
+                return p.C ? (char*)p.C + ((long long)row * p.ldc + n0) * esz : nullptr;
+            };
+            auto epilogue = [&](auto tag) {
+                using T = decltype(tag);                              // float or __bf16
+                constexpr int esz = sizeof(T);
+                typedef __attribute__((__vector_size__(4 * sizeof(T)))) T Tx4;
+                typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+                if (fast) {
+                    // stage 32 rows x BN columns per pass in this wave's own part of LDS, then move whole
+                    // 16-byte chunks of rows to C: full cache lines per store instruction
+                    constexpr int pitch = BN * esz + 16;
+                    constexpr int cpr = BN * esz / 16;                // 16-byte chunks per row
+                    unsigned char* stage = lds + wave * 32 * pitch;
+                    unsigned char* wr = stage + (lane_e & 31) * pitch + 4 * (lane_e >> 5) * esz;
+                    static_for<MB>([&](auto i_c) {
+                        constexpr int i = decltype(i_c)::value;
+                        static_for<NB * 4>([&](auto jq_c) {
+                            constexpr int j = decltype(jq_c)::value / 4, qd = decltype(jq_c)::value % 4;
+                            constexpr int r0 = (i * NB + j) * 16 + qd * 4;
+                            const float x0 = acc_read<r0>(), x1 = acc_read<r0 + 1>(), x2 = acc_read<r0 + 2>(),
+                                        x3 = acc_read<r0 + 3>();
+                            *(Tx4*)(wr + (j * 32 + qd * 8) * esz) = Tx4{(T)x0, (T)x1, (T)x2, (T)x3};
+                        });
+                        // the same wave wrote and reads: LDS keeps a wave's operations in order
+                        for (int c = lane_e; c < 32 * cpr; c += 64) {
+                            const int r = c / cpr, cc = c - r * cpr;
+                            const u32x4 val = *(const u32x4*)(stage + r * pitch + cc * 16);
+                            char* dst = row_ptr(row_w + i * 32 + r, esz);
+                            if (dst) *(u32x4*)(dst + cc * 16) = val;
+                        }
+                    });
+                } else {
+                    // edge tiles and unaligned outputs: one element at a time, constant offsets from one row pointer
+                    static_for<MB>([&](auto i_c) {
+                        constexpr int i = decltype(i_c)::value;
+                        char* dst = row_ptr(row_w + i * 32 + (lane_e & 31), esz);
+                        const int col0 = n0 + 4 * (lane_e >> 5);
+                        T* q = (T*)dst + 4 * (lane_e >> 5);
+                        static_for<NB * 16>([&](auto jv_c) {
+                            constexpr int j = decltype(jv_c)::value / 16, v = decltype(jv_c)::value % 16;
+                            constexpr int off = j * 32 + 8 * (v >> 2) + (v & 3);
+                            const float x = acc_read<(i * NB + j) * 16 + v>();
+                            if (dst && col0 + off < p.N) q[off] = (T)x;
+                        });
+                    });
                 }
+            };
+            if (p.c_is_f32) epilogue(float{}); else epilogue(__bf16{});
         }
 
         // GEMM-RS: count finished tiles of the own slice; the last one raises the producer signal
@@ -280,7 +452,17 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p)
         // the ring is reused by the next tile: drain this tile's last (redundant) loads and reads first
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
         __syncthreads();
+#ifdef AGG_EXP_TIMING
+        if (tid == 0 && (g == 0 || g == 100)) {
+            const long long tt3 = __builtin_readcyclecounter();
+            long long* dbg = (long long*)(p.err + 8) + (g ? 4 : 0);
+            dbg[0] = tt1 - tt0; dbg[1] = tt2 - tt1; dbg[2] = tt3 - tt2; dbg[3] = KT;
+        }
+#endif
     }
+#else
+    (void)p;
+#endif
 }
 
 template <int BM, int BN, int NS>
@@ -302,8 +484,7 @@ hipError_t launch_gemm(const GemmParams& p, int cfg, int grid, hipStream_t strea
 {
     switch (cfg) {
         case TILE_256x224: return launch_cfg<256, 224, 4>(p, grid, stream);
-        case TILE_256x256: return launch_cfg<256, 256, 4>(p, grid, stream);
-        default: return launch_cfg<128, 128, 4>(p, grid, stream);
+        default: return launch_cfg<128, 128, 6>(p, grid, stream);
     }
 }
 

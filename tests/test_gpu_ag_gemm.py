@@ -62,7 +62,7 @@ def test_tiny_bit_identical_over_all_arrival_orders_and_launch_orders():
         run.close()
 
 
-@pytest.mark.parametrize("tile", [0, 2])
+@pytest.mark.parametrize("tile", [0, 1])
 def test_integer_inputs_are_exact(tile):
     # entries in {-2..2}: every partial sum is an integer below 2^24, so fp32 accumulation is exact
     inp = wl.make_ag_gemm(wl.AG_RAGGED, a_dist=("int", 2), b_dist=("int", 2))
@@ -87,7 +87,7 @@ def test_identity_b_returns_gathered_a_bit_exactly():
         run.close()
 
 
-@pytest.mark.parametrize("tile", [0, 2])
+@pytest.mark.parametrize("tile", [0, 1])
 @pytest.mark.parametrize("chunks", [1, 4])
 def test_ragged_shape_f32_and_bf16(tile, chunks):
     inp = wl.make_ag_gemm(wl.AG_RAGGED)         # M=600, N=328, K=320: ragged against every tile shape
