@@ -31,7 +31,7 @@ typedef struct agg_ctx agg_ctx;
 enum {
     AGG_OK = 0,
     AGG_ERR_INVALID_ARG = -1,       /* null pointer, negative size, rank outside [0, W) ... */
-    AGG_ERR_UNSUPPORTED_SHAPE = -2, /* K not a multiple of 32, M not a multiple of W, shard larger than T ... */
+    AGG_ERR_UNSUPPORTED_SHAPE = -2, /* K not a multiple of 64, M not a multiple of W, shard larger than T ... */
     AGG_ERR_MISALIGNED = -3,        /* a pointer or leading dimension breaks the 16-byte rule */
     AGG_ERR_HIP = -4,               /* a HIP runtime call failed (the HIP error is cleared) */
     AGG_ERR_TIMEOUT = -5,           /* a kernel gave up waiting for a signal (reported by agg_status) */
@@ -123,7 +123,7 @@ int ag_producer_emulate(agg_ctx* ctx, const void* const* remote_shards, const in
  * dimension ldb (elements), C row-major with leading dimension ldc (elements) of type c_dtype.
  * Accumulation is fp32; bf16 output is rounded to nearest even from the fp32 accumulator.
  * Each tile waits (acquire) for every signal covering its rows to reach the current epoch before its
- * first load of A.  Requirements: K % 32 == 0, M % W == 0, ldb % 8 == 0, B 16-byte aligned,
+ * first load of A.  Requirements: K % 64 == 0, M % W == 0, ldb % 8 == 0, B 16-byte aligned,
  * C aligned to its element size; M, N arbitrary (>= 0; 0 is a no-op).
  */
 int ag_gemm(agg_ctx* ctx, int M, int N, int K,

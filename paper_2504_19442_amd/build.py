@@ -21,7 +21,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-i
          "-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"]
 
 
-def check_agprs(extra_flags=()) -> None:
+def check_agprs(extra_flags=(), allow_scratch=False) -> None:
     """Compile the GEMM kernel to assembly and fail if the compiler itself touches an accumulator register
     (any a<N> outside the inline-asm blocks), or if a kernel spills to scratch."""
     import re
@@ -42,7 +42,7 @@ def check_agprs(extra_flags=()) -> None:
             code = t.split(";")[0]
             if pat.search(code):
                 raise RuntimeError(f"compiler-allocated accumulator register in gemm_kernel (asm line {n}): {t}")
-        if t.startswith("; ScratchSize:") and t.split(":")[1].strip() != "0":
+        if t.startswith("; ScratchSize:") and t.split(":")[1].strip() != "0" and not allow_scratch:
             raise RuntimeError(f"gemm_kernel spills to scratch: {t}")
 
 
@@ -64,7 +64,7 @@ def _compile(src: str) -> str:
 def build_variant(out_path: str, extra_flags: list) -> str:
     """Build the same sources with extra compiler flags into out_path (kernel experiments; never the product)."""
     import tempfile
-    check_agprs(extra_flags)
+    check_agprs(extra_flags, allow_scratch=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     with tempfile.TemporaryDirectory() as tmp:
         objs = []

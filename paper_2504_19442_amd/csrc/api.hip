@@ -72,7 +72,7 @@ int check_gemm_operands(int M, int N, int K, const void* B, int ldb, int b_layou
     if (M == 0 || N == 0) return AGG_OK;
     if (!B || !C) return AGG_ERR_INVALID_ARG;
     if (b_layout != AGG_B_NK) return AGG_ERR_UNSUPPORTED_SHAPE;
-    if (K == 0 || K % 32 != 0 || K > (1 << 21)) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (K == 0 || K % 64 != 0 || K > (1 << 21)) return AGG_ERR_UNSUPPORTED_SHAPE;
     if (ldb < K || ldc < N) return AGG_ERR_INVALID_ARG;
     if (ldb % 8 != 0 || !aligned16(B)) return AGG_ERR_MISALIGNED;
     if (reinterpret_cast<uintptr_t>(C) % (c_dtype == AGG_F32 ? 4 : 2) != 0) return AGG_ERR_MISALIGNED;
@@ -286,7 +286,10 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     p.wait_ticks = wait_ticks(c);
     p.err = c->err;
     const long long tiles = (long long)p.tiles_m * p.tiles_n;
-    const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
+    int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
+#ifdef AGG_EXP_GRID
+    grid = AGG_EXP_GRID;
+#endif
     return hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)consumer_stream));
 }
 

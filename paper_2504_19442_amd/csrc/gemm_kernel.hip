@@ -8,14 +8,17 @@
 // the workgroup waits (acquire) for the signals covering the tile's rows -- the wait / consume_token
 // pair of Section 2.2.
 //
-// Main loop: K is cut into steps of 32.  A and B tiles go from global memory straight into LDS
-// (buffer_load_dwordx4 ... lds, 16 bytes per lane) through a ring of NS stages, so NS-1 steps of loads are
-// in flight while one is computed.  Rows are 64 bytes in LDS; the 16-byte chunk c of row r sits in slot
-// c ^ ((r >> 2) & 3), which makes the ds_read_b128 operand fetches bank-conflict free.  Each wave owns
-// BM/4 rows and all BN columns of the tile and feeds v_mfma_f32_32x32x16_bf16 from register sets of
-// fragments that are refilled one half-step ahead of their use.  One workgroup barrier per step.  The
-// fragment reads and global->LDS loads of a step are dealt out one per MFMA (a wave issues in order and a
-// memory instruction is slow to issue, so bunches of them between two MFMAs starve the matrix pipe).
+// Main loop: K is cut into stages of 64, so that every row of a tile is fetched as one whole 128-byte line
+// (the L2 hands out lines: asking for half a line at a time halves its useful bandwidth, and the loop was
+// bound by exactly that).  A and B tiles go from global memory straight into LDS (buffer_load_dwordx4 ... lds,
+// 16 bytes per lane) into one of two stage buffers.  Rows are 128 bytes in LDS; the 16-byte chunk c of row r
+// sits in slot c ^ ((r >> 1) & 7), which makes the ds_read_b128 operand fetches bank-conflict free.  Each
+// wave owns BM/4 rows and all BN columns of the tile and feeds v_mfma_f32_32x32x16_bf16; a stage is four
+// quarter-steps of K=16, and the fragments of a quarter-step are read from LDS while the previous one is on
+// the matrix pipe (two register sets).  One workgroup barrier per stage, placed before the last quarter-step:
+// by then every wave has read all it needs of the current stage, so the loads of the stage after next can
+// start into its buffer at once.  Memory instructions are dealt out one per MFMA (a wave issues in order
+// and a memory instruction is slow to issue, so bunches of them between two MFMAs starve the matrix pipe).
 // The MFMA computes the transposed block (B fragment as first operand), so that a lane ends up holding
 // four consecutive columns of one output row; the epilogue stages each wave's rows through LDS and
 // stores them to C as whole 16-byte row chunks.
@@ -81,11 +84,12 @@ __device__ __forceinline__ float acc_read()
     return x;
 }
 
-constexpr int BK = 32;                 // bf16 per K-step
-constexpr int ROW_BYTES = BK * 2;      // 64-byte rows in LDS
-constexpr int UNIT_ROWS = 16;          // one wave-wide 16-byte-per-lane load covers 16 rows
+constexpr int BK = 64;                 // bf16 per stage
+constexpr int ROW_BYTES = BK * 2;      // 128-byte rows in LDS: one cache line per row and stage
+constexpr int UNIT_ROWS = 8;           // one wave-wide 16-byte-per-lane load covers 8 rows
+[[maybe_unused]] constexpr int QS = 4;   // quarter-steps (K = 16 each) per stage
 
-template <int BM, int BN, int NS>
+template <int BM, int BN>
 struct Cfg {
     static constexpr int TM = BM / 4;            // rows per wave
     static constexpr int MB = TM / 32;           // 32x32 blocks per wave, M direction
@@ -94,44 +98,35 @@ struct Cfg {
     static constexpr int A_UNITS = BM / UNIT_ROWS;
     static constexpr int B_UNITS = BN / UNIT_ROWS;
     static constexpr int UNITS = A_UNITS + B_UNITS;
-    static constexpr int FULL = UNITS / 4;       // whole units per wave per stage
-    static constexpr int REM = UNITS % 4;        // 0, or 2 (each of the two left-over units is loaded by a pair of waves: same data twice)
-    static constexpr int L = FULL + (REM ? 1 : 0);   // load instructions per wave per stage
+    static constexpr int L = UNITS / 4;          // load instructions per wave per stage
     static constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
-    static constexpr int LDS_BYTES = STAGE_BYTES * NS;
-    static_assert(BM % 128 == 0 && BN % 32 == 0, "tile shape");
-    static_assert(A_UNITS % 4 == 0, "A units must split evenly over 4 waves");
-    static_assert(REM == 0 || REM == 2, "unsupported unit count");
-    static_assert(NS >= 3 && NS % 2 == 0, "ring needs at least 3 stages, and an even count for the fragment-set rotation");
-    static_assert((NS - 2) * L <= 63, "vmcnt range");
-    static_assert(ACC == 64 || ACC == 128 || ACC == 224 || ACC == 256, "add a reservation line for this accumulator count");
-    // MFMA slots of one K-step: [0, SLOTS_A) before the barrier, then the rest of half-step 0, then half-step 1
-    // (slots [SLOTS/2, SLOTS)).  A wave issues in order, and a memory instruction takes long enough to issue
-    // that more than one or two of them between two MFMAs leaves the matrix pipe idle; so every slot gets at
-    // most QUOTA memory instructions.  First half of the step: the F = MB+NB fragment reads of half-step 1,
-    // then L1 of the step's global->LDS loads; second half: the F fragment reads of the next step's
-    // half-step 0, then the remaining loads.
-    static constexpr int H = NB / 2;
-    static constexpr int SLOTS = 2 * MB * NB;
-    static constexpr int SLOTS_A = MB * H;
-    static constexpr int F = MB + NB;
-    static constexpr int QUOTA = (2 * F + L + SLOTS - 1) / SLOTS;
-    static constexpr int CAP = (SLOTS / 2) * QUOTA;              // memory instructions per half
-    static constexpr int L1 = (L < CAP - F) ? L : CAP - F;       // loads issued in the first half
-    static_assert(CAP >= F && F + (L - L1) <= CAP, "memory instructions do not fit the slots");
-    static_assert(F / QUOTA >= SLOTS_A, "the first load of a step must come after the barrier");
     // epilogue staging: each wave stages 32 rows x BN columns at a time
     static constexpr int PITCH_BF16 = BN * 2 + 16;
     static constexpr int PITCH_F32 = BN * 4 + 16;
-    static_assert(4 * 32 * PITCH_F32 <= LDS_BYTES, "epilogue staging does not fit in the ring");
+    static constexpr int LDS_BYTES = (2 * STAGE_BYTES > 4 * 32 * PITCH_F32) ? 2 * STAGE_BYTES : 4 * 32 * PITCH_F32;
+    static_assert(BM % 128 == 0 && BN % 32 == 0, "tile shape");
+    static_assert(A_UNITS % 4 == 0 && B_UNITS % 4 == 0, "units must split evenly over 4 waves");
+    static_assert(L <= 63, "vmcnt range");
+    static_assert(ACC == 64 || ACC == 128 || ACC == 224 || ACC == 256, "add a reservation line for this accumulator count");
+    // One quarter-step is SLOTS = MB*NB MFMAs.  Its memory instructions, in order: LQ global->LDS loads
+    // (while a stage's loads are being issued: the three quarter-steps after a barrier), then the F = MB+NB
+    // fragment reads of the next quarter-step.  They are dealt out QUOTA per MFMA slot.
+    static constexpr int SLOTS = MB * NB;
+    static constexpr int F = MB + NB;
+#ifndef AGG_LOAD_QUARTERS
+#define AGG_LOAD_QUARTERS 3
+#endif
+    static constexpr int LQ = (L + AGG_LOAD_QUARTERS - 1) / AGG_LOAD_QUARTERS;   // loads per quarter-step while a batch is issued
+    static constexpr int QUOTA = (LQ + F + SLOTS - 1) / SLOTS;
 };
 
-template <int BM, int BN, int NS>
+// Register budget: 448 of the 512 registers a SIMD has (see the file comment).
+template <int BM, int BN>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gemm_kernel(const GemmParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)    // the body names gfx950 registers; the host pass only needs the launch stub
-    using C_ = Cfg<BM, BN, NS>;
-    constexpr int MB = C_::MB, NB = C_::NB, L = C_::L, FULL = C_::FULL, TM = C_::TM;
+    using C_ = Cfg<BM, BN>;
+    constexpr int MB = C_::MB, NB = C_::NB, L = C_::L, TM = C_::TM;
     // naming the last accumulator register makes the compiler reserve a0..a(ACC-1) for this kernel
     if constexpr (C_::ACC == 256) asm volatile("; accumulators a0..a255" ::: "a255");
     else if constexpr (C_::ACC == 224) asm volatile("; accumulators a0..a223" ::: "a223");
@@ -144,16 +139,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // ---- per-lane constants
-    // global->LDS: lane l of a unit fills row l/4, slot l%4; the slot holds chunk (l%4) ^ ((row>>2)&3)
-    const int ld_row = lane >> 2;
-    const int ld_chunk = (lane & 3) ^ ((lane >> 4) & 3);
-    // LDS->VGPR fragments: lane l reads row l%32, chunk 2*s + l/32, stored in slot chunk ^ ((row>>2)&3)
-    int fr_off[2];
+    // global->LDS: lane l of a unit fills row l/8, slot l%8 of the unit's 8 rows; slot s of row r holds chunk
+    // s ^ ((r >> 1) & 7).  With r = 8u + l/8 that is s ^ ((4u + l/16) & 7): two cases, u even and u odd.
+    const int ld_row = lane >> 3;
+    const int ld_chunk_even = (lane & 7) ^ ((lane >> 4) & 7);
+    const int ld_chunk_odd = (lane & 7) ^ ((4 + (lane >> 4)) & 7);
+    // LDS->VGPR fragments of quarter-step h: lane l reads row l%32, chunk 2h + l/32, from slot chunk ^ ((row>>1)&7)
+    int fr_off[QS];
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
-        fr_off[s] = (lane & 31) * ROW_BYTES + (((2 * s + (lane >> 5)) ^ ((lane >> 2) & 3)) << 4);
+    for (int h = 0; h < QS; ++h)
+        fr_off[h] = (lane & 31) * ROW_BYTES + (((2 * h + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
 
-    const int KT = p.K / BK;
+    const int KS = p.K / BK;             // stages
     const int total_tiles = p.tiles_m * p.tiles_n;
     const int G = gridDim.x;
     const int g = blockIdx.x;
@@ -197,10 +194,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                 }
             }
             if (gave_up) __hip_atomic_store(p.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#ifndef AGG_EXP_NO_ACQ
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#endif
             if (__syncthreads_or(gave_up)) return;   // the launch drains; agg_status reports the time-out
+            // Every signal has been seen: acquire, so that no load of A below is served from a line cached
+            // before the data arrived.  The acquire invalidates this CU's L1 and this XCD's L2 lines of
+            // remotely written memory; one wave does it for the workgroup (invalidates from all waves of all
+            // CUs queue up behind each other at the L2), the barrier holds the others back until it is done.
+            if (wave == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            __syncthreads();
         }
 
         // ---- per-tile buffer descriptors and per-lane load offsets (bytes from the tile's A / B origin);
@@ -209,80 +209,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             make_rsrc(p.A + (long long)m0 * p.lda, (unsigned)(min(BM, p.M - m0) * (int)p.lda * 2));
         const __amdgpu_buffer_rsrc_t b_rsrc =
             make_rsrc(p.B + (long long)n0 * p.ldb, (unsigned)(min(BN, p.N - n0) * (int)p.ldb * 2));
+        // unit i of this wave is unit u = wave + 4i of the stage: A units first, then B units
         unsigned ld_off[L];
 #pragma unroll
         for (int i = 0; i < L; ++i) {
-            const int u = (i < FULL) ? wave + 4 * i : 4 * FULL + (wave >> 1);
-            if (u < C_::A_UNITS)
-                ld_off[i] = (unsigned)((u * UNIT_ROWS + ld_row) * (int)p.lda * 2 + ld_chunk * 16);
+            const int u = wave + 4 * i;
+            const int chunk = (u & 1) ? ld_chunk_odd : ld_chunk_even;
+            if (4 * i < C_::A_UNITS)
+                ld_off[i] = (unsigned)((u * UNIT_ROWS + ld_row) * (int)p.lda * 2 + chunk * 16);
             else
-                ld_off[i] = (unsigned)(((u - C_::A_UNITS) * UNIT_ROWS + ld_row) * (int)p.ldb * 2 + ld_chunk * 16);
+                ld_off[i] = (unsigned)(((u - C_::A_UNITS) * UNIT_ROWS + ld_row) * (int)p.ldb * 2 + chunk * 16);
         }
 
-        // one global->LDS load (unit i of this wave) of K-step kt into stage st
-        auto load_unit = [&](int i, int st, int kt) {
-            const int u = (i < FULL) ? wave + 4 * i : 4 * FULL + (wave >> 1);
-            // whether unit i of this wave is an A or a B unit is the same for all four waves
-            const bool is_a = ((i < FULL) ? 4 * i : 4 * FULL) < C_::A_UNITS;
-#ifdef AGG_EXP_SAME_M0
-            unsigned char* dst = lds + st * C_::STAGE_BYTES + (u & 3) * 1024;
-#else
-            unsigned char* dst = lds + st * C_::STAGE_BYTES + u * 1024;
-#endif
-#if defined(AGG_EXP_MB1)
-            // microbenchmark-like addressing, step 1: one descriptor, private rows per wave, 2 KiB window
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, LDS_PTR(dst), 16,
-                                                     (unsigned)((wave * 64 + i * 16 + ld_row) * 16384 + ld_chunk * 16) % (3u << 20),
-                                                     (kt & 31) * ROW_BYTES, 0, 0);
-#elif defined(AGG_EXP_MB2)
-            // step 2: real descriptors and offsets, but the K offset cycles inside a 2 KiB window
+        // one global->LDS load (unit i of this wave) of stage ks into buffer buf
+        auto load_unit = [&](int i, int buf, int ks) {
+            const int u = wave + 4 * i;
+            const bool is_a = 4 * i < C_::A_UNITS;      // the same for all four waves
+            unsigned char* dst = lds + buf * C_::STAGE_BYTES + u * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
-                                                     (kt & 31) * ROW_BYTES, 0, 0);
-#elif defined(AGG_EXP_MB3)
-            // step 3: real K offsets, one descriptor
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, LDS_PTR(dst), 16,
-                                                     (unsigned)((wave * 64 + i * 16 + ld_row) * 16384 + ld_chunk * 16) % (3u << 20),
-                                                     kt * ROW_BYTES, 0, 0);
-#elif defined(AGG_EXP_MB4)
-            // real offsets, one descriptor
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, LDS_PTR(dst), 16, ld_off[i], kt * ROW_BYTES, 0, 0);
-#elif defined(AGG_EXP_MB5)
-            // two descriptors, wave-private rows
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16,
-                                                     (unsigned)((wave * 64 + i * 16 + ld_row) * 16384 + ld_chunk * 16) % (3u << 20),
-                                                     kt * ROW_BYTES, 0, 0);
-#elif defined(AGG_EXP_MB6)
-            // two descriptors, real row ranges, rows contiguous per wave
-            {
-                const int unit = is_a ? wave * 4 + i : min(wave * 4 + (i - 4), C_::B_UNITS - 1);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16,
-                                                         (unsigned)((unit * 16 + ld_row) * 16384 + ld_chunk * 16),
-                                                         kt * ROW_BYTES, 0, 0);
-            }
-#elif defined(AGG_EXP_MB7)
-            // real pattern but B rows taken from the A tile region +256 rows (distinct lines, A descriptor)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, LDS_PTR(dst), 16, ld_off[i] + (is_a ? 0u : 0u),
-                                                     kt * ROW_BYTES + (is_a ? 0 : 8192 * 2 * 0), 0, 0);
-#elif defined(AGG_EXP_SAME_K)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
-                                                     (kt & 1) * ROW_BYTES, 0, 0);
-#elif defined(AGG_EXP_LOAD_VGPR)
-            typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4_;
-            u32x4_ v_ = __builtin_amdgcn_raw_buffer_load_b128(is_a ? a_rsrc : b_rsrc, ld_off[i], kt * ROW_BYTES, 0);
-            asm volatile("" ::"v"(v_));
-            (void)dst;
-#else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
-                                                     kt * ROW_BYTES, 0, 0);
-#endif
+                                                     ks * ROW_BYTES, 0, 0);
         };
 
-        // three fragment sets: sets 0 and 1 alternate for half-step 0 (the next step's is fetched while the
-        // current one is still being used), set 2 serves half-step 1.  Fragment f < MB is the A fragment of
-        // row block f, fragment MB + j the B fragment of column block j.
-        bf16x8 fr[3][MB + NB];
-        auto read_frag = [&](int f, int st, int s, int set) {
-            const unsigned char* src = lds + st * C_::STAGE_BYTES + fr_off[s] +
+        // two fragment sets, one per parity of the quarter-step.  Fragment f < MB is the A fragment of row
+        // block f, fragment MB + j the B fragment of column block j.
+        bf16x8 fr[2][MB + NB];
+        auto read_frag = [&](int f, int buf, int h, int set) {
+            const unsigned char* src = lds + buf * C_::STAGE_BYTES + fr_off[h] +
                                        (f < MB ? (wave * TM + f * 32) * ROW_BYTES : (BM + (f - MB) * 32) * ROW_BYTES);
             fr[set][f] = *(const bf16x8*)src;
         };
@@ -292,13 +244,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 #endif
         static_for<C_::ACC>([&](auto r) { acc_zero<decltype(r)::value>(); });
 
-        // ---- prologue: NS-1 stages in flight (steps past the end re-load the last step: harmless, and it
-        // keeps the number of outstanding loads per wave the same on every path)
+        // ---- prologue: both stage buffers in flight (a stage past the end re-loads the last one: harmless,
+        // and it keeps the number of outstanding loads per wave the same on every path)
 #pragma unroll
-        for (int st = 0; st < NS - 1; ++st)
+        for (int i = 0; i < L; ++i) load_unit(i, 0, 0);
 #pragma unroll
-            for (int i = 0; i < L; ++i) load_unit(i, st, min(st, KT - 1));
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * L));
+        for (int i = 0; i < L; ++i) load_unit(i, 1, min(1, KS - 1));
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(L));
         __builtin_amdgcn_s_barrier();
 #pragma unroll
         for (int f = 0; f < MB + NB; ++f) read_frag(f, 0, 0, 0);
@@ -314,65 +266,75 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 #else
 #define LOOP_LOAD_UNIT(...) load_unit(__VA_ARGS__)
 #endif
-        // ---- main loop, unrolled over the ring so that stage and set indices are constants.  The MFMAs are
-        // volatile asm, so memory operations keep their place between them: the interleaving below is the
-        // schedule.  Slot q of a half-step works on column block q / MB, row block q % MB; the B fragment is
-        // the first MFMA operand, so accumulator block (i, j) holds the transposed 32x32 block.
 #ifdef AGG_EXP_TIMING
         const long long tt1 = __builtin_readcyclecounter();
 #endif
-        for (int kt0 = 0;; kt0 += NS) {
+        // ---- main loop, two stages per pass so that buffer indices are constants.  The MFMAs are volatile
+        // asm, so memory operations keep their place between them: the order below is the schedule.  Slot q of
+        // a quarter-step works on column block q / MB, row block q % MB; the B fragment is the first MFMA
+        // operand, so accumulator block (i, j) holds the transposed 32x32 block.
+        //
+        // Stage ks in buffer b: quarter-steps 0..2 read ahead inside b; then every wave waits for its loads of
+        // stage ks+1 and meets at the barrier -- all of stage ks+1 is in LDS and nobody needs buffer b any
+        // more; quarter-step 3 reads the first fragments of stage ks+1 from the other buffer.  The loads of
+        // stage ks+2 go into b, LOAD_SLOTS per quarter-step, starting right after the barrier.
+        for (int ks0 = 0;; ks0 += 2) {
             bool done = false;
-            static_for<NS>([&](auto st_c) {
-                constexpr int st = decltype(st_c)::value;
-                constexpr int cur = st & 1, nxt = (st + 1) & 1;
+            static_for<2>([&](auto b_c) {
+                constexpr int b = decltype(b_c)::value;
                 if (done) return;
-                const int kt = kt0 + st;
-                const int kt_load = min(kt + NS - 1, KT - 1);
-                // the memory instructions that follow the MFMA of slot `slot`
-                auto mem_after = [&](auto slot_c) {
-                    constexpr int slot = decltype(slot_c)::value;
-                    constexpr bool second = slot >= C_::SLOTS / 2;
-                    static_for<C_::QUOTA>([&](auto k_c) {
-                        constexpr int o = (slot % (C_::SLOTS / 2)) * C_::QUOTA + decltype(k_c)::value;
-                        if constexpr (o < C_::F) {
-                            // fragment reads: half-step 1 of this step, or half-step 0 of the next step
-                            if constexpr (!second) LOOP_READ_FRAG(o, st, 1, 2);
-                            else LOOP_READ_FRAG(o, (st + 1) % NS, 0, nxt);
-                        } else {
-                            // global->LDS loads of step kt+NS-1 into the stage every wave finished reading
-                            // before the barrier of this step
-                            constexpr int i = (second ? C_::L1 : 0) + o - C_::F;
-                            if constexpr (i < (second ? L : C_::L1)) LOOP_LOAD_UNIT(i, (st + NS - 1) % NS, kt_load);
-                        }
+                const int ks = ks0 + b;
+                const int ks_load_prev = min(ks + 1, KS - 1);     // the batch begun in the previous stage's last quarter
+                const int ks_load = min(ks + 2, KS - 1);
+                static_for<QS>([&](auto h_c) {
+                    constexpr int h = decltype(h_c)::value;
+                    constexpr int set = h & 1;
+                    static_for<C_::SLOTS>([&](auto q_c) {
+                        constexpr int q = decltype(q_c)::value;
+                        mfma_acc<(q % MB) * NB + q / MB>(fr[set][MB + q / MB], fr[set][q % MB]);
+                        static_for<C_::QUOTA>([&](auto k_c) {
+                            constexpr int o = q * C_::QUOTA + decltype(k_c)::value;
+                            if constexpr (h == QS - 2) {
+                                // the quarter before the barrier issues no loads: its fragment reads go first, so
+                                // that they are back when the wave reaches the barrier
+                                if constexpr (o < C_::F) LOOP_READ_FRAG(o, b, h + 1, 1 - set);
+                            } else if constexpr (o < C_::LQ) {
+                                // quarter 3 starts the batch for stage ks+2 (into this buffer, free since the
+                                // barrier); quarters 0 and 1 finish the batch for stage ks+1 begun in the
+                                // previous stage's last quarter
+                                if constexpr (h == QS - 1) {
+                                    if constexpr (o < L) LOOP_LOAD_UNIT(o, b, ks_load);
+                                } else {
+                                    constexpr int i = (h + 1) * C_::LQ + o;
+                                    if constexpr (i < L) LOOP_LOAD_UNIT(i, 1 - b, ks_load_prev);
+                                }
+                            } else if constexpr (o - C_::LQ < C_::F) {
+                                constexpr int f = o - C_::LQ;
+                                if constexpr (h < QS - 1) LOOP_READ_FRAG(f, b, h + 1, 1 - set);
+                                else LOOP_READ_FRAG(f, 1 - b, 0, 1 - set);
+                            }
+                        });
                     });
-                };
-                static_for<C_::SLOTS>([&](auto q_c) {
-                    constexpr int slot = decltype(q_c)::value;
-                    constexpr int set = slot < C_::SLOTS / 2 ? cur : 2;
-                    constexpr int q = slot % (C_::SLOTS / 2);       // column block q / MB, row block q % MB
-                    mfma_acc<(q % MB) * NB + q / MB>(fr[set][MB + q / MB], fr[set][q % MB]);
-                    mem_after(q_c);
-                    if constexpr (slot == C_::SLOTS_A - 1) {
+                    if constexpr (h == QS - 2) {
 #ifndef AGG_EXP_NO_BARRIER
-                        // stage kt+1 has landed for this wave once at most the younger stages are outstanding;
-                        // after the barrier it has landed for all waves, and all waves are done with stage kt-1
-                        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * L));
+                        // stage ks+1 has landed for this wave, its own fragment reads of this stage are back;
+                        // after the barrier that holds for all waves
+                        __builtin_amdgcn_s_waitcnt(0);      // vmcnt(0) expcnt(0) lgkmcnt(0)
                         __builtin_amdgcn_s_barrier();
 #endif
                     }
                 });
-                if (kt + 1 >= KT) done = true;
+                if (ks + 1 >= KS) done = true;
             });
             if (done) break;
         }
+#ifdef AGG_EXP_TIMING
+        const long long tt2 = __builtin_readcyclecounter();
+#endif
 
         // ---- epilogue.  Accumulator block (i, j) is the transposed block: lane l holds output row
         // i*32 + l%32 and, in register v, column j*32 + 8*(v/4) + 4*(l/32) + v%4 -- four consecutive columns per
         // group of four registers.
-#ifdef AGG_EXP_TIMING
-        const long long tt2 = __builtin_readcyclecounter();
-#endif
         asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7");     // the last MFMAs retire before the read-out
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));              // the last (redundant) loads have landed in LDS
         __syncthreads();                                       // and every wave is done with the ring
@@ -398,8 +360,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                     // 16-byte chunks of rows to C: full cache lines per store instruction
                     constexpr int pitch = BN * esz + 16;
                     constexpr int cpr = BN * esz / 16;                // 16-byte chunks per row
+                    constexpr int iters = (32 * cpr + 63) / 64;       // chunk c = lane + 64*it: row c / cpr, chunk c % cpr
                     unsigned char* stage = lds + wave * 32 * pitch;
                     unsigned char* wr = stage + (lane_e & 31) * pitch + 4 * (lane_e >> 5) * esz;
+                    const int r_lane = lane_e / cpr, cc_lane = lane_e - r_lane * cpr;
                     static_for<MB>([&](auto i_c) {
                         constexpr int i = decltype(i_c)::value;
                         static_for<NB * 4>([&](auto jq_c) {
@@ -409,13 +373,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                                         x3 = acc_read<r0 + 3>();
                             *(Tx4*)(wr + (j * 32 + qd * 8) * esz) = Tx4{(T)x0, (T)x1, (T)x2, (T)x3};
                         });
-                        // the same wave wrote and reads: LDS keeps a wave's operations in order
-                        for (int c = lane_e; c < 32 * cpr; c += 64) {
-                            const int r = c / cpr, cc = c - r * cpr;
-                            const u32x4 val = *(const u32x4*)(stage + r * pitch + cc * 16);
-                            char* dst = row_ptr(row_w + i * 32 + r, esz);
-                            if (dst) *(u32x4*)(dst + cc * 16) = val;
-                        }
+                        // the same wave wrote and reads: LDS keeps a wave's operations in order.  GRP chunks at a
+                        // time: their LDS reads first (independent registers), then their stores.
+                        const int row0 = row_w + i * 32;
+                        // the 32 rows go to C, or (GEMM-RS) all to this rank's own slot; a block that straddles
+                        // the slot boundary takes the per-row route
+                        const bool own_all = p.C_own && row0 >= p.own_lo && row0 + 32 <= p.own_hi;
+                        const bool own_none = !p.C_own || row0 + 32 <= p.own_lo || row0 >= p.own_hi;
+                        char* base = own_all ? (char*)p.C_own + ((long long)(row0 - p.own_lo) * p.ldc_own + n0) * esz
+                                             : (p.C ? (char*)p.C + ((long long)row0 * p.ldc + n0) * esz : nullptr);
+                        const unsigned ld_bytes = (unsigned)((own_all ? p.ldc_own : p.ldc) * esz);
+                        const int rows_ok = min(32, p.M - row0);
+                        constexpr int GRP = 7;
+                        int r = r_lane, cc = cc_lane;
+                        static_for<(iters + GRP - 1) / GRP>([&](auto g_c) {
+                            constexpr int it0 = decltype(g_c)::value * GRP;
+                            constexpr int n = (iters - it0 < GRP) ? iters - it0 : GRP;
+                            u32x4 val[n];
+                            int rs[n], ccs[n];
+                            static_for<n>([&](auto k_c) {
+                                constexpr int k = decltype(k_c)::value;
+                                rs[k] = r;
+                                ccs[k] = cc;
+                                if (r < 32) val[k] = *(const u32x4*)(stage + r * pitch + cc * 16);
+                                // next chunk of this lane: 64 chunks further on
+                                cc += 64 % cpr;
+                                r += 64 / cpr;
+                                if (cc >= cpr) { cc -= cpr; r += 1; }
+                            });
+                            static_for<n>([&](auto k_c) {
+                                constexpr int k = decltype(k_c)::value;
+                                if (own_all || own_none) {
+                                    if (base && rs[k] < rows_ok)
+                                        *(u32x4*)(base + (unsigned)rs[k] * ld_bytes + (unsigned)ccs[k] * 16u) = val[k];
+                                } else {
+                                    char* dst = rs[k] < 32 ? row_ptr(row0 + rs[k], esz) : nullptr;
+                                    if (dst) *(u32x4*)(dst + ccs[k] * 16) = val[k];
+                                }
+                            });
+                        });
                     });
                 } else {
                     // edge tiles and unaligned outputs: one element at a time, constant offsets from one row pointer
@@ -449,14 +445,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             }
         }
 
-        // the ring is reused by the next tile: drain this tile's last (redundant) loads and reads first
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __syncthreads();
+        // the stage buffers are reused by the next tile: every wave must be done with its staging reads first.
+        // The C stores need not be waited for: the next tile's waits count them as well, which only makes
+        // those waits stricter.
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only (vmcnt and expcnt fields at their no-wait maximum)
+        __builtin_amdgcn_s_barrier();
 #ifdef AGG_EXP_TIMING
         if (tid == 0 && (g == 0 || g == 100)) {
             const long long tt3 = __builtin_readcyclecounter();
             long long* dbg = (long long*)(p.err + 8) + (g ? 4 : 0);
-            dbg[0] = tt1 - tt0; dbg[1] = tt2 - tt1; dbg[2] = tt3 - tt2; dbg[3] = KT;
+            dbg[0] = tt1 - tt0; dbg[1] = tt2 - tt1; dbg[2] = tt3 - tt2; dbg[3] = KS;
         }
 #endif
     }
@@ -465,26 +463,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 #endif
 }
 
-template <int BM, int BN, int NS>
+template <int BM, int BN>
 static hipError_t launch_cfg(const GemmParams& p, int grid, hipStream_t stream)
 {
-    using C_ = Cfg<BM, BN, NS>;
+    using C_ = Cfg<BM, BN>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<BM, BN, NS>,
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<BM, BN>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C_::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, NS>), dim3(grid), dim3(256), C_::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN>), dim3(grid), dim3(256), C_::LDS_BYTES, stream, p);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm(const GemmParams& p, int cfg, int grid, hipStream_t stream)
 {
     switch (cfg) {
-        case TILE_256x224: return launch_cfg<256, 224, 4>(p, grid, stream);
-        default: return launch_cfg<128, 128, 6>(p, grid, stream);
+        case TILE_256x224: return launch_cfg<256, 224>(p, grid, stream);
+        default: return launch_cfg<128, 128>(p, grid, stream);
     }
 }
 
