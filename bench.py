@@ -141,18 +141,32 @@ def main() -> int:
             agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, cons)
             agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
 
-        n2 = max(10, args.steps // 2)
-        t_gemm = timed(step_gemm, n2, 3)
-        t_copy = timed(step_copy, n2, 3)
-        t_serial = timed(step_serial, n2, 3)
+        # alternate the four measurements over several rounds (clocks drift with load and temperature: taking
+        # them one after the other would bias the ratios), medians of the rounds are reported
+        def step_fused_plain():
+            step_fused(None)
+
+        n2, rounds = max(5, args.steps // 5), 5
+        acc = {"fused": [], "gemm": [], "copy": [], "serial": []}
+        for _ in range(rounds):
+            ev_cons_done.record(cons)
+            acc["fused"].append(timed(step_fused_plain, n2, 2))
+            agg.signal_reset(ctx)
+            step_copy()
+            torch.cuda.synchronize()            # signals of this epoch are set: the GEMM alone does not wait
+            acc["gemm"].append(timed(step_gemm, n2, 2))
+            acc["copy"].append(timed(step_copy, n2, 2))
+            acc["serial"].append(timed(step_serial, n2, 2))
         assert agg.agg_status(ctx) == agg.OK
+        t_fused2, t_gemm, t_copy, t_serial = (float(np.median(acc[k])) for k in ("fused", "gemm", "copy", "serial"))
         out["overlap"] = {
-            "t_fused_ms": round(t_fused * 1e3, 4), "t_gemm_ms": round(t_gemm * 1e3, 4),
+            "t_fused_ms": round(t_fused2 * 1e3, 4), "t_gemm_ms": round(t_gemm * 1e3, 4),
             "t_copy_ms": round(t_copy * 1e3, 4), "t_serial_ms": round(t_serial * 1e3, 4),
-            "overlap_efficiency": round(t_serial / t_fused, 4),
-            "hidden_fraction": round((t_serial - t_fused) / t_copy, 4),
+            "overlap_efficiency": round(t_serial / t_fused2, 4),
+            "hidden_fraction": round((t_serial - t_fused2) / t_copy, 4),
             "gemm_alone_tflops": round(flops / t_gemm / 1e12, 2),
-            "fused_over_gemm": round(t_fused / t_gemm, 4),
+            "fused_over_gemm": round(t_fused2 / t_gemm, 4),
+            "protocol": f"medians of {rounds} alternating rounds of {n2} steps",
         }
         # the reducer of GEMM+ReduceScatter at its full size (all signals set: pure streaming reduction)
         rs = wl.RS_FULL

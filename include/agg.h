@@ -108,7 +108,7 @@ int agg_status(agg_ctx* ctx);
  * each r in arrival_order (HOST array of n_arrivals ranks, each != rank, no repeats; NULL = the rotated
  * order rank+1, rank+2, ... and n_arrivals is ignored), L_r is copied to T + r*shard_bytes chunk by chunk
  * and each chunk's signal is set (release) once the chunk has landed.  Shards not listed never arrive.
- * mode: AGG_PRODUCER_KERNEL uses `n_workgroups` workgroups (0 = default 32) whose registers fit beside
+ * mode: AGG_PRODUCER_KERNEL uses `n_workgroups` workgroups (0 = one per compute unit) whose registers fit beside
  * the consumer's on every CU; AGG_PRODUCER_SDMA uses hipMemcpyAsync without compute units.
  */
 int ag_producer_emulate(agg_ctx* ctx, const void* const* remote_shards, const int* arrival_order,
@@ -134,6 +134,8 @@ int ag_gemm(agg_ctx* ctx, int M, int N, int K,
  * ReduceScatter reduction (Algorithm 3, stream 2): R = sum_{w=0}^{W-1} slot_w, fp32, in the order
  * w = 0, 1, .., W-1 starting from +0, whatever the arrival order.  Before reading slot w the kernel waits
  * for signal w * (n_signals / W) to reach the current epoch.
+ * A waiting reducer occupies compute units: whatever raises the signals must be able to run beside it
+ * (copies, signal_set and this library's producer can; a kernel that needs every register of a CU cannot).
  * slots: HOST array of W device pointers to fp32 [Ms, N] row-major (leading dimension N).
  * R: [Ms, N] of r_dtype, leading dimension ldr.  Ms * N must be a multiple of 4; slots 16-byte aligned.
  */
@@ -146,8 +148,9 @@ int rs_reduce(agg_ctx* ctx, int Ms, int N, const float* const* slots,
  * out, un-gated), computing this rank's row slice [rank*Ms, (rank+1)*Ms) first and writing it straight
  * into slots[rank]; when that slice is complete its signal is set (the producer signal of Algorithm 3).
  * The other rows go to P_other (fp32 [M, N], leading dimension N; rows of the own slice are not written;
- * may be NULL to skip computing them).  Enqueues on reduce_stream the reduction of rs_reduce, which
- * waits for every slot's signal.  Peers' slots "arrive" when the caller sets their signals
+ * may be NULL to skip computing them).  Enqueues on reduce_stream a stream-level wait for the own slot's
+ * signal (it holds no compute unit, so the GEMM can always become resident) and then the reduction of
+ * rs_reduce, which waits for every slot's signal and runs beside the rest of the GEMM.  Peers' slots "arrive" when the caller sets their signals
  * (signal_set, or a producer of the caller's own).
  */
 int gemm_rs(agg_ctx* ctx, int M, int N, int Klocal,

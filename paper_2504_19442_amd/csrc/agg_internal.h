@@ -65,6 +65,7 @@ struct ProducerArgs {
     int* flags;
     int* counters;
     int epoch;
+    int team;                     // workgroups that share one chunk (set by launch_producer)
 };
 hipError_t launch_producer(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_signal_set(int* flag, int value, hipStream_t stream);
@@ -104,4 +105,6 @@ struct agg_ctx {
     int device;
     int tile_config;     // -1 = automatic
     hipStream_t producer_stream, consumer_stream;
+    int can_wait_value;  // the device supports stream waits on a memory word
+    hipEvent_t gemm_done; // GEMM-RS: orders the reducer after the GEMM where it does not
 };

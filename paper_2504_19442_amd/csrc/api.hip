@@ -107,6 +107,11 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     if ((rc = hip_fail(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device))) != AGG_OK) goto fail;
     c->num_cus = prop.multiProcessorCount;
     c->wall_khz = khz > 0 ? khz : 100000;
+    {
+        int can = 0;
+        if (hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, c->device) != hipSuccess) (void)hipGetLastError();
+        c->can_wait_value = can;
+    }
     if ((rc = hip_fail(hipMalloc((void**)&c->staging, (size_t)world_size * shard_bytes))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMalloc((void**)&c->signals, sig_bytes))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMalloc((void**)&c->counters, ctr_bytes))) != AGG_OK) goto fail;
@@ -118,6 +123,7 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     if ((rc = hip_fail(hipMemset(c->epoch_word, 0, 256))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipStreamCreateWithFlags(&c->producer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipStreamCreateWithFlags(&c->consumer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipEventCreateWithFlags(&c->gemm_done, hipEventDisableTiming))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) goto fail;
     *out = c;
     return AGG_OK;
@@ -132,6 +138,7 @@ int symm_free(agg_ctx* c)
     (void)hipDeviceSynchronize();
     if (c->producer_stream) (void)hipStreamDestroy(c->producer_stream);
     if (c->consumer_stream) (void)hipStreamDestroy(c->consumer_stream);
+    if (c->gemm_done) (void)hipEventDestroy(c->gemm_done);
     if (c->staging) (void)hipFree(c->staging);
     if (c->signals) (void)hipFree(c->signals);
     if (c->counters) (void)hipFree(c->counters);
@@ -235,7 +242,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     a.epoch = c->epoch;
     hipStream_t st = (hipStream_t)producer_stream;
     if (mode == AGG_PRODUCER_KERNEL) {
-        const int nwg = n_workgroups > 0 ? n_workgroups : 32;
+        const int nwg = n_workgroups > 0 ? n_workgroups : c->num_cus;
         return hip_fail(launch_producer(a, nwg, st));
     }
     // copy engine: one transfer per chunk, then "another data transfer solely for signals" (Section 3.6)
@@ -286,10 +293,7 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     p.wait_ticks = wait_ticks(c);
     p.err = c->err;
     const long long tiles = (long long)p.tiles_m * p.tiles_n;
-    int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
-#ifdef AGG_EXP_GRID
-    grid = AGG_EXP_GRID;
-#endif
+    const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
     return hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)consumer_stream));
 }
 
@@ -325,8 +329,9 @@ int rs_reduce(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int
     a.err = c->err;
     int nwg = n_workgroups;
     if (nwg == 0) {
-        const long long need = (a.n_vec4 + 256 * 4 - 1) / (256 * 4);
-        nwg = (int)(need < (long long)c->num_cus * 8 ? need : (long long)c->num_cus * 8);
+        // persistent: a few workgroups per CU, each walking many blocks (one acquire per workgroup, not per block)
+        const long long need = (a.n_vec4 + 255) / 256;
+        nwg = (int)(need < (long long)c->num_cus * 4 ? need : (long long)c->num_cus * 4);
         if (nwg < 1) nwg = 1;
     }
     return hip_fail(launch_reduce(a, nwg, (hipStream_t)stream));
@@ -398,6 +403,23 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
     const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
     rc = hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)gemm_stream));
     if (rc != AGG_OK) return rc;
+    // The reducer waits for this rank's own slot, which the GEMM above produces.  A reducer that spun for that
+    // signal inside the kernel could hold the registers the GEMM's workgroups still need to become resident, and
+    // the two would wait for each other; so the reduce stream itself waits (no compute unit is held) until the own
+    // slice is signalled, and the reducer then runs beside the rest of the GEMM.  The stream wait ends at the
+    // latest when the GEMM kernel has completed, so it needs no time limit of its own.
+    if (gemm_stream != reduce_stream) {
+        bool waited = false;
+        if (c->can_wait_value) {
+            waited = hipStreamWaitValue32((hipStream_t)reduce_stream, p.done_flag, (uint32_t)c->epoch, hipStreamWaitValueGte,
+                                          0xFFFFFFFFu) == hipSuccess;
+            if (!waited) (void)hipGetLastError();
+        }
+        if (!waited) {   // no stream wait on memory here: order the reducer after the whole GEMM
+            if ((rc = hip_fail(hipEventRecord(c->gemm_done, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
+            if ((rc = hip_fail(hipStreamWaitEvent((hipStream_t)reduce_stream, c->gemm_done, 0))) != AGG_OK) return rc;
+        }
+    }
     return rs_reduce(c, Ms, N, slots, R, ldr, r_dtype, 0, reduce_stream);
 }
 

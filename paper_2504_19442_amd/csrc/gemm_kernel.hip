@@ -434,7 +434,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 
         // GEMM-RS: count finished tiles of the own slice; the last one raises the producer signal
         if (p.done_ctr && m0 < p.own_hi && m0 + BM > p.own_lo) {
-            __syncthreads();     // all stores of this tile issued
+            __builtin_amdgcn_s_waitcnt(0);   // this wave's stores of the tile have reached L2 ...
+            __syncthreads();                 // ... and so have every other wave's, before thread 0 publishes them
             if (tid == 0) {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
                 const int prev = __hip_atomic_fetch_add(p.done_ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);

@@ -8,44 +8,59 @@ namespace agg {
 
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 
+// The grid is cut into teams of `team` workgroups.  Chunks are numbered in arrival order (all chunks of
+// the first shard to arrive, then the next shard's, ...); team t copies chunks t, t + n_teams, ... and
+// inside a team each workgroup copies one contiguous slice of the chunk; several chunks are in flight at
+// once, which is also how a full mesh of links delivers (Section 3.7).
+//
+// The stores are write-through at system scope (sc0 sc1): the data goes to memory instead of staying
+// dirty in the L2 of the XCD the workgroup happens to run on, so no L2 write-back is needed before the
+// signal -- a wait for the stores to complete is the release.  (An agent-scope release fence would write
+// back the whole L2, once per workgroup and chunk, and that cost more than the copy itself.)  The consumer's
+// acquire invalidates its own L2 lines, so its loads fetch the data from memory.
 __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
 {
     const int tid = threadIdx.x;
-    const int nwg = gridDim.x;
+    const int team = a.team;
+    const int n_teams = gridDim.x / team;
+    const int t = blockIdx.x / team, j = blockIdx.x - t * team;
+    if (t >= n_teams) return;                       // left-over workgroups of a grid that is not a multiple of team
     const long long vec_per_chunk = a.chunk_bytes / 16;
-    const long long stride = (long long)nwg * 256;
-    for (int j = 0; j < a.n_jobs; ++j) {
-        const int r = a.rank_of[j];
-        const u32x4* src = (const u32x4*)a.src[j];
-        u32x4* dst = (u32x4*)(a.T + (long long)r * a.shard_bytes);
-        for (int c = 0; c < a.chunks_per_shard; ++c) {
-            const u32x4* s = src + c * vec_per_chunk;
-            u32x4* d = dst + c * vec_per_chunk;
-            long long i = (long long)blockIdx.x * 256 + tid;
-            // four independent 16-byte loads in flight per lane; streaming (non-temporal) accesses keep
-            // the copy from evicting the consumer's tiles from L2
-            for (; i + 3 * stride < vec_per_chunk; i += 4 * stride) {
-                u32x4 v0 = __builtin_nontemporal_load(s + i);
-                u32x4 v1 = __builtin_nontemporal_load(s + i + stride);
-                u32x4 v2 = __builtin_nontemporal_load(s + i + 2 * stride);
-                u32x4 v3 = __builtin_nontemporal_load(s + i + 3 * stride);
-                __builtin_nontemporal_store(v0, d + i);
-                __builtin_nontemporal_store(v1, d + i + stride);
-                __builtin_nontemporal_store(v2, d + i + 2 * stride);
-                __builtin_nontemporal_store(v3, d + i + 3 * stride);
-            }
-            for (; i < vec_per_chunk; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
-            // signal: the last workgroup to finish the chunk sets it (set_signal after the copy, Algorithm 2)
-            __syncthreads();
-            if (tid == 0) {
-                const int f = r * a.chunks_per_shard + c;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                const int prev = __hip_atomic_fetch_add(a.counters + f, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-                if (prev == nwg - 1) {
-                    __hip_atomic_store(a.counters + f, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(a.flags + (long long)f * kSignalStride, a.epoch, __ATOMIC_RELEASE,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-                }
+    const long long per_wg = (vec_per_chunk + team - 1) / team;
+    const long long lo = j * per_wg, hi = lo + per_wg < vec_per_chunk ? lo + per_wg : vec_per_chunk;
+    const int n_chunks = a.n_jobs * a.chunks_per_shard;
+    constexpr int NT = 2, WT = 1 | 16 | 2;          // cache policy bits: nt (streaming); sc0 | sc1 | nt (write-through)
+    for (int ch = t; ch < n_chunks; ch += n_teams) {
+        const int job = ch / a.chunks_per_shard, c = ch - job * a.chunks_per_shard;
+        const int r = a.rank_of[job];
+        // this workgroup's slice [lo, hi) of the chunk, as buffers of at most (hi - lo) * 16 < 2^31 bytes
+        const char* s = (const char*)a.src[job] + (c * vec_per_chunk + lo) * 16;
+        char* d = a.T + (long long)r * a.shard_bytes + (c * vec_per_chunk + lo) * 16;
+        const unsigned bytes = hi > lo ? (unsigned)((hi - lo) * 16) : 0u;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(s), 0, bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(d, 0, bytes, 0x00020000);
+        // four independent 16-byte loads in flight per lane; out-of-range lanes of the last round load zero
+        // and store nothing (the descriptors bound both)
+        for (unsigned off = tid * 16u; off < bytes; off += 4u * 4096u) {
+            u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, NT);
+            u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 4096u, 0, NT);
+            u32x4 v2 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 8192u, 0, NT);
+            u32x4 v3 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 12288u, 0, NT);
+            __builtin_amdgcn_raw_buffer_store_b128(v0, rd, off, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v1, rd, off + 4096u, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v2, rd, off + 8192u, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v3, rd, off + 12288u, 0, WT);
+        }
+        // signal: the last workgroup of the team to finish the chunk sets it (set_signal after the copy, Algorithm 2)
+        __builtin_amdgcn_s_waitcnt(0);              // every store of this lane has completed
+        __syncthreads();                            // ... of this workgroup
+        if (tid == 0) {
+            const int f = r * a.chunks_per_shard + c;
+            const int prev = __hip_atomic_fetch_add(a.counters + f, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (prev == team - 1) {
+                __hip_atomic_store(a.counters + f, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.flags + (long long)f * kSignalStride, a.epoch, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
@@ -56,8 +71,14 @@ __global__ void signal_set_kernel(int* flag, int value)
     __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-hipError_t launch_producer(const ProducerArgs& a, int n_workgroups, hipStream_t stream)
+hipError_t launch_producer(const ProducerArgs& a_in, int n_workgroups, hipStream_t stream)
 {
+    ProducerArgs a = a_in;
+    // team size: slices of at least 64 KiB, at most the whole grid on one chunk
+    long long team = a.chunk_bytes / 65536;
+    if (team < 1) team = 1;
+    if (team > n_workgroups) team = n_workgroups;
+    a.team = (int)team;
     hipLaunchKernelGGL(producer_kernel, dim3(n_workgroups), dim3(256), 0, stream, a);
     return hipGetLastError();
 }

@@ -10,7 +10,6 @@ namespace agg {
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 
-constexpr int RU = 4;   // float4 per lane per slot kept in flight
 
 __device__ inline bool wait_signal(const int* fp, int epoch, long long ticks, int* err)
 {
@@ -44,32 +43,75 @@ __device__ inline void store_out(const ReduceArgs& a, long long i, f32x4 v)
     }
 }
 
+// WT > 0: the world size is the compile-time constant WT (loops over slots unroll, all loads of a block are in
+// flight together); WT == 0: any world size.
+template <int WT, int RU>   // RU = float4 per lane per slot and block
 __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
 {
     const int tid = threadIdx.x;
+    const int W = WT > 0 ? WT : a.W;
     const long long stride = (long long)gridDim.x * 256;
-    int seen = 0;                      // slots 0..seen-1 are known to have arrived
+    int seen = 0;                      // slots 0..seen-1 are known to have arrived (uniform over the workgroup)
     for (long long base = (long long)blockIdx.x * 256 + tid; base - tid < a.n_vec4; base += stride * RU) {
         f32x4 acc[RU];
 #pragma unroll
         for (int u = 0; u < RU; ++u) acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int w = 0; w < a.W; ++w) {
-            if (w >= seen) {           // uniform over the workgroup: `seen` only changes here
-                int ok = 1;
-                if (tid == 0) ok = wait_signal(a.flags + (long long)w * a.flag_step * kSignalStride, a.epoch, a.wait_ticks, a.err);
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-                if (__syncthreads_or(!ok)) return;
-                seen = w + 1;
-            }
-            const f32x4* s = (const f32x4*)a.slot[w];
-            f32x4 v[RU];
+        if (seen < W) {
+            // slots still to arrive: take them one by one in the order of Algorithm 3.  A wait that ends also
+            // looks at the signals after it, so that one acquire (an L2 invalidate) covers all that are set.
+            for (int w = 0; w < W; ++w) {
+                if (w >= seen) {
+                    int ok = 1, upto = w + 1;
+                    if (tid == 0) {
+                        ok = wait_signal(a.flags + (long long)w * a.flag_step * kSignalStride, a.epoch, a.wait_ticks, a.err);
+                        while (ok && upto < W &&
+                               __hip_atomic_load(a.flags + (long long)upto * a.flag_step * kSignalStride, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT) >= a.epoch)
+                            ++upto;
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                    }
+                    upto = __builtin_amdgcn_readfirstlane(upto);      // thread 0 is lane 0 of wave 0
+                    __shared__ int s_upto;
+                    if (tid == 0) s_upto = upto;
+                    if (__syncthreads_or(!ok)) return;
+                    seen = s_upto;
+                    __syncthreads();
+                }
+                const f32x4* s = (const f32x4*)a.slot[w];
 #pragma unroll
-            for (int u = 0; u < RU; ++u) {
-                const long long i = base + u * stride;
-                v[u] = (i < a.n_vec4) ? __builtin_nontemporal_load(s + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int u = 0; u < RU; ++u) {
+                    const long long i = base + u * stride;
+                    const f32x4 v = (i < a.n_vec4) ? __builtin_nontemporal_load(s + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+                    acc[u] = acc[u] + v;                              // R = R + T[w], one fp32 rounding each
+                }
             }
+        } else {
+            // every slot has arrived: all loads of the block first, then the additions in slot order
+            if constexpr (WT > 0) {
+                f32x4 v[WT][RU];
 #pragma unroll
-            for (int u = 0; u < RU; ++u) acc[u] = acc[u] + v[u];      // R = R + T[w], one fp32 rounding each
+                for (int w = 0; w < WT; ++w)
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) {
+                        const long long i = base + u * stride;
+                        v[w][u] = (i < a.n_vec4) ? __builtin_nontemporal_load((const f32x4*)a.slot[w] + i)
+                                                 : f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                for (int w = 0; w < WT; ++w)
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) acc[u] = acc[u] + v[w][u];
+            } else {
+                for (int w = 0; w < W; ++w) {
+                    const f32x4* s = (const f32x4*)a.slot[w];
+#pragma unroll
+                    for (int u = 0; u < RU; ++u) {
+                        const long long i = base + u * stride;
+                        const f32x4 v = (i < a.n_vec4) ? __builtin_nontemporal_load(s + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+                        acc[u] = acc[u] + v;
+                    }
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
@@ -81,7 +123,12 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
 
 hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream)
 {
-    hipLaunchKernelGGL(reduce_kernel, dim3(n_workgroups), dim3(256), 0, stream, a);
+    switch (a.W) {
+        case 8: hipLaunchKernelGGL((reduce_kernel<8, 1>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
+        case 4: hipLaunchKernelGGL((reduce_kernel<4, 2>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
+        case 2: hipLaunchKernelGGL((reduce_kernel<2, 4>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
+        default: hipLaunchKernelGGL((reduce_kernel<0, 2>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
+    }
     return hipGetLastError();
 }
 

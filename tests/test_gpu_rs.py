@@ -1,0 +1,248 @@
+"""GPU parity of the ReduceScatter reducer and of GEMM-ReduceScatter against the CPU oracle, through the C ABI.
+
+Bars: the reducer is bit-exact against the oracle's ordered fp32 sum (Algorithm 3, stream 2) whatever the order
+in which the slots' signals are raised; GEMM-RS is within rel. Frobenius 1e-4 and max abs 1e-3*sqrt(K)*scale of
+the fp64 oracle, and bit-identical across signal orders.
+"""
+import itertools
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2504_19442_amd as agg
+import workloads as wl
+from gpu_util import dev_bf16, host_bits
+
+pytestmark = pytest.mark.gpu
+
+
+class RsRun:
+    """W fp32 slots on the device (poisoned until they 'arrive'), a context and its stream pair."""
+
+    def __init__(self, W, rank, Ms, N, n_signals=None):
+        self.W, self.rank, self.Ms, self.N = W, rank, Ms, N
+        self.ctx = agg.symm_alloc(W, rank, 16, n_signals or W)
+        self.step = (n_signals or W) // W
+        ps, cs = self.ctx.streams()
+        self.prod = torch.cuda.ExternalStream(ps)
+        self.cons = torch.cuda.ExternalStream(cs)
+        self.slots = [torch.full((Ms, N), float("nan"), device="cuda", dtype=torch.float32) for _ in range(W)]
+
+    def deliver(self, w, data, sleep=0.0):
+        """Slot w arrives: its data lands (on the producer stream), then its signal is raised."""
+        if sleep:
+            time.sleep(sleep)
+        with torch.cuda.stream(self.prod):
+            self.slots[w].copy_(data, non_blocking=True)
+        agg.signal_set(self.ctx, w * self.step, self.prod)
+
+    def poison(self):
+        for s in self.slots:
+            s.fill_(float("nan"))
+        torch.cuda.synchronize()
+
+    def status_ok(self):
+        torch.cuda.synchronize()
+        st = agg.agg_status(self.ctx)
+        assert st == agg.OK, agg.agg_strerror(st)
+
+    def close(self):
+        self.ctx.free()
+
+
+def _slots_with_cancellation(W, Ms, N, seed):
+    """fp32 slots whose sum depends on the order of the additions (mixed magnitudes and signs)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for w in range(W):
+        mag = np.float32(10.0) ** rng.integers(-3, 5, size=(Ms, N)).astype(np.float32)
+        out.append((rng.standard_normal((Ms, N)).astype(np.float32) * mag).astype(np.float32))
+    return out
+
+
+@pytest.mark.parametrize("W,Ms,N", [(4, 64, 192), (8, 33, 100), (3, 7, 36), (1, 5, 8), (2, 130, 260), (5, 64, 64)])
+def test_reducer_bit_exact_in_any_signal_order(W, Ms, N):
+    data = _slots_with_cancellation(W, Ms, N, seed=7000 + W)
+    want = oracle.rs_reduce_f32(data)
+    # the order matters for these values: a reversed fp32 sum differs somewhere (the test would not see a wrong order otherwise)
+    if W > 2:
+        assert not np.array_equal(want, oracle.rs_reduce_f32(data[::-1]))
+    dev = [torch.from_numpy(d).cuda() for d in data]
+    run = RsRun(W, 0, Ms, N)
+    try:
+        orders = list(itertools.permutations(range(W)))
+        rng = np.random.default_rng(1)
+        picks = [orders[0], orders[-1]] + [orders[i] for i in rng.choice(len(orders), size=min(4, len(orders)), replace=False)]
+        for k, order in enumerate(picks):
+            run.poison()
+            agg.signal_reset(run.ctx)
+            R = torch.full((Ms, N), float("nan"), device="cuda", dtype=torch.float32)
+            torch.cuda.synchronize()
+            if k % 2 == 0:       # reducer launched first: it must wait for every slot
+                agg.rs_reduce(run.ctx, Ms, N, run.slots, R, N, agg.F32, 0, run.cons)
+                for w in order:
+                    run.deliver(w, dev[w], sleep=0.002 if k == 0 else 0.0)
+            else:
+                for w in order:
+                    run.deliver(w, dev[w])
+                agg.rs_reduce(run.ctx, Ms, N, run.slots, R, N, agg.F32, 0, run.cons)
+            run.status_ok()
+            got = R.cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"order {order}"
+    finally:
+        run.close()
+
+
+def test_reducer_bf16_output_strided_and_workgroup_counts():
+    W, Ms, N = 4, 48, 72
+    data = _slots_with_cancellation(W, Ms, N, seed=7100)
+    want32 = oracle.rs_reduce_f32(data)
+    want16 = wl.f32_to_bf16_bits(want32)
+    dev = [torch.from_numpy(d).cuda() for d in data]
+    run = RsRun(W, 2, Ms, N, n_signals=3 * W)     # several signals per shard: slot w uses the first of its group
+    try:
+        for nwg in (0, 1, 3, 1000):
+            for dtype, ldr in ((agg.BF16, N), (agg.BF16, N + 8), (agg.F32, N + 4)):
+                run.poison()
+                agg.signal_reset(run.ctx)
+                tdt = torch.bfloat16 if dtype == agg.BF16 else torch.float32
+                R = torch.zeros((Ms, ldr), device="cuda", dtype=tdt)
+                torch.cuda.synchronize()
+                agg.rs_reduce(run.ctx, Ms, N, run.slots, R, ldr, dtype, nwg, run.cons)
+                for w in (3, 1, 0, 2):
+                    run.deliver(w, dev[w])
+                run.status_ok()
+                if dtype == agg.BF16:
+                    got = host_bits(R)
+                    assert np.array_equal(got[:, :N], want16)
+                    assert not got[:, N:].any()                       # padding columns untouched
+                else:
+                    got = R.cpu().numpy()
+                    assert np.array_equal(got[:, :N].view(np.uint32), want32.view(np.uint32))
+                    assert not got[:, N:].any()
+    finally:
+        run.close()
+
+
+def test_reducer_times_out_when_a_slot_never_arrives():
+    W, Ms, N = 4, 16, 32
+    run = RsRun(W, 0, Ms, N)
+    try:
+        run.ctx.set_wait_limit_us(20000)
+        agg.signal_reset(run.ctx)
+        R = torch.zeros((Ms, N), device="cuda", dtype=torch.float32)
+        zero = torch.zeros((Ms, N), device="cuda", dtype=torch.float32)
+        agg.rs_reduce(run.ctx, Ms, N, run.slots, R, N, agg.F32, 0, run.cons)
+        for w in (0, 1, 3):                       # slot 2 never arrives
+            run.deliver(w, zero)
+        torch.cuda.synchronize()
+        assert agg.agg_status(run.ctx) == agg.ERR_TIMEOUT
+        assert agg.agg_status(run.ctx) == agg.OK  # the record is cleared by the first status call
+    finally:
+        run.close()
+
+
+def test_reducer_argument_errors():
+    run = RsRun(4, 0, 8, 8)
+    try:
+        R = torch.zeros((8, 8), device="cuda", dtype=torch.float32)
+        with pytest.raises(agg.AggError):
+            agg.rs_reduce(run.ctx, 8, 8, run.slots[:3] + [None], R, 8, agg.F32)       # a null slot
+        with pytest.raises(agg.AggError):
+            agg.rs_reduce(run.ctx, 8, 8, run.slots, R, 4, agg.F32)                    # ldr < N
+        with pytest.raises(agg.AggError):
+            agg.rs_reduce(run.ctx, 3, 3, run.slots, R, 3, agg.F32)                    # 9 elements: not a multiple of 4
+        with pytest.raises(agg.AggError):
+            agg.rs_reduce(run.ctx, 8, 8, run.slots, R, 8, 7)                          # unknown dtype
+        agg.rs_reduce(run.ctx, 0, 8, run.slots, R, 8, agg.F32)                        # empty: a no-op
+        run.status_ok()
+    finally:
+        run.close()
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# GEMM + ReduceScatter
+# ----------------------------------------------------------------------------------------------------------------
+
+def _gemm_rs_case(shape, rank, rows_own, rows_other, tile=None, with_other=True, orders=1):
+    inp = wl.make_gemm_rs(shape, rank=rank)
+    W, M, Ms, Kl, N = shape.W, shape.M, shape.Ms, shape.Kl, shape.N
+    A = dev_bf16(inp.A_loc)
+    B_nk = dev_bf16(np.ascontiguousarray(inp.B_kn.T))
+    peers = {w: torch.from_numpy(s).cuda() for w, s in inp.peer_slots.items()}
+    run = RsRun(W, rank, Ms, N)
+    results = []
+    try:
+        if tile is not None:
+            run.ctx.set_tile_config(tile)
+        others = [w for w in range(W) if w != rank]
+        rng = np.random.default_rng(11)
+        for k in range(orders):
+            order = others if k == 0 else list(rng.permutation(others))
+            run.poison()
+            agg.signal_reset(run.ctx)
+            P = torch.full((M, N), float("nan"), device="cuda", dtype=torch.float32) if with_other else None
+            R = torch.full((Ms, N), float("nan"), device="cuda", dtype=torch.float32)
+            torch.cuda.synchronize()
+            # the peers' partial sums arrive on the GEMM's stream: before the launch (odd runs) or after it (even runs);
+            # the reducer, on the other stream, is launched before the late ones exist
+            if k % 2 == 1:
+                for w in order:
+                    run.deliver(w, peers[w])
+            agg.gemm_rs(run.ctx, M, N, Kl, A, Kl, B_nk, Kl, agg.B_NK, run.slots, P, R, N, agg.F32, run.prod, run.cons)
+            if k % 2 == 0:
+                for w in order:
+                    run.deliver(w, peers[w])
+            run.status_ok()
+            results.append((R.cpu().numpy(), None if P is None else P))
+        R0 = results[0][0]
+        for Rk, _ in results[1:]:
+            assert np.array_equal(Rk.view(np.uint32), R0.view(np.uint32))
+        # own slice + peers against the fp64 oracle
+        want = oracle.gemm_rs(inp.A_loc, inp.B_kn, inp.peer_slots, W, rank, rows=rows_own)
+        got = R0[rows_own].astype(np.float64)
+        scale = max(1.0, float(np.abs(want).max()))
+        rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+        assert rel <= 1e-4, rel
+        assert np.abs(got - want).max() <= 1e-3 * np.sqrt(Kl) * scale
+        # the slot the GEMM wrote is exactly what the reducer added: R - peers (in order) is reproducible on the host
+        own = run.slots[rank].cpu().numpy()
+        ordered = [inp.peer_slots[w] if w != rank else own for w in range(W)]
+        assert np.array_equal(oracle.rs_reduce_f32(ordered).view(np.uint32), R0.view(np.uint32))
+        if with_other:
+            P = results[0][1]
+            rows_other = np.asarray(rows_other)
+            wantP = oracle.gemm(inp.A_loc, inp.B_kn, rows=rows_other)
+            gotP = P[torch.from_numpy(rows_other).cuda()].cpu().numpy().astype(np.float64)
+            relP = np.linalg.norm(gotP - wantP) / max(np.linalg.norm(wantP), 1e-30)
+            assert relP <= 1e-4, relP
+            # rows of the own slice are never written to P_other
+            assert torch.isnan(P[rank * Ms:(rank + 1) * Ms]).all()
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("rank", [0, 1, 3])
+@pytest.mark.parametrize("tile", [0, 1])
+def test_gemm_rs_tiny(rank, tile):
+    sh = wl.RS_TINY
+    rows_other = [r for r in range(sh.M) if not (rank * sh.Ms <= r < (rank + 1) * sh.Ms)]
+    _gemm_rs_case(sh, rank, np.arange(sh.Ms), rows_other, tile=tile, orders=3)
+
+
+def test_gemm_rs_own_slice_only():
+    sh = wl.RS_TINY
+    _gemm_rs_case(sh, 2, np.arange(sh.Ms), [], with_other=False, orders=2)
+
+
+def test_gemm_rs_full_size_sampled_rows():
+    sh = wl.RS_FULL
+    rank = 5
+    rng = np.random.default_rng(5)
+    rows_own = np.sort(rng.choice(sh.Ms, size=12, replace=False))
+    rows_other = np.sort(rng.choice(np.setdiff1d(np.arange(sh.M), np.arange(rank * sh.Ms, (rank + 1) * sh.Ms)),
+                                    size=12, replace=False))
+    _gemm_rs_case(sh, rank, rows_own, rows_other, orders=2)
