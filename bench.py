@@ -20,6 +20,19 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak (published)
 
 
+def _measured_traffic(workload: str):
+    """HBM bytes per GEMM launch measured with rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy of
+    known size); read from the committed summary of that measurement, None if there is none for this workload."""
+    path = os.path.join(ROOT, "profiles", f"gemm_kernel_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -29,7 +42,10 @@ def main() -> int:
     ap.add_argument("--tile", type=int, default=-1)
     ap.add_argument("--chunks", type=int, default=4, help="signals per shard")
     ap.add_argument("--producer-wgs", type=int, default=0)
-    ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of C the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="profiling aid: also run one plain 256 MiB device copy, the known-size kernel that the "
+                         "FETCH_SIZE / WRITE_SIZE counters are scaled by")
     ap.add_argument("--no-extras", action="store_true", help="skip the reducer / serial / copy-only timings")
     ap.add_argument("--shape", default="", help="profiling aid: W,Ms,K,N of an ad-hoc AllGather-GEMM shape")
     ap.add_argument("--only-gemm", action="store_true",
@@ -97,6 +113,14 @@ def main() -> int:
         run.close()
         return 0
 
+    if args.pmc_calibration:
+        src = torch.ones(256 << 20, device="cuda", dtype=torch.uint8)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     ev_cons_done.record(cons)
     # ---- the headline: fused step
     for _ in range(args.warmup):
@@ -124,7 +148,7 @@ def main() -> int:
         "fraction_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": {"bound": "mfma", "achieved": round(flops / (kern_ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(flops / (kern_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None, "kernel": "gemm_kernel (signal-gated, fused run)",
+                     "traffic": _measured_traffic(shape.name), "kernel": "gemm_kernel (signal-gated, fused run)",
                      "kernel_ms": round(kern_ms, 4)},
     }
 
