@@ -165,7 +165,14 @@ int gemm_rs(agg_ctx* ctx, int M, int N, int Klocal,
  * Y[p, :] = X[token(p), :] . W_expert(p) for the p-th pair, Y [Ttok*topk, N] row-major of y_dtype.
  * weights: bf16 [E][N][K] (K contiguous per expert).  sorted_token / sorted_expert_offsets are DEVICE
  * outputs the call fills (int32 [Ttok*topk] and int32 [E+1]) and then uses; the caller may read them.
- * Each tile waits for the signals of every shard its gathered tokens come from.
+ * A tile lies inside one expert's segment and waits for the signals of the rows of T between its first and its
+ * last token (tokens rise inside a segment, so that range holds every token of the tile).
+ * Requirements: K % 64 == 0, Ttok % W == 0, shard_bytes == (Ttok / W) * K * 2, Ttok * K * 2 < 2 GiB, weights 16-byte
+ * aligned, ldy >= N.  Ids outside [0, E) are skipped: their pairs appear nowhere and
+ * sorted_expert_offsets[E] is then smaller than Ttok * topk.  Rows of Y past sorted_expert_offsets[E] are not
+ * written.  Routing and GEMM run on `stream`; routing does not depend on T and runs before any signal is awaited.
+ * The first call (and any call with a larger problem) allocates the context's tile table and synchronises the
+ * device; later calls allocate nothing.
  */
 int ag_moe_gemm(agg_ctx* ctx, int Ttok, int topk, int E, int N, int K,
                 const int32_t* topk_ids, const void* weights,

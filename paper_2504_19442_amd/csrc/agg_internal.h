@@ -39,7 +39,35 @@ struct GemmParams {
     int* done_ctr;
     int done_target;
     int* done_flag;
+    // grouped (MoE) GEMM only: rows of A are gathered through row_index, tiles come from a table built on the device
+    const int* row_index;         // row p of the output reads row row_index[p] of A
+    const struct MoeTile* tile_tab;
+    const int* n_tiles_dev;       // number of table entries (device word)
+    long long b_group_stride;     // elements between the B matrices of consecutive groups (experts)
+    unsigned a_bytes;             // size of A in bytes (bound of the gather)
 };
+
+// One output tile of the grouped GEMM: rows [m0, m_end) of the sorted pair list (inside one expert's segment),
+// columns of n-tile n_tile, waiting for signals f_lo..f_hi.
+struct MoeTile {
+    int expert, m0, m_end, n_tile, f_lo, f_hi, pad0, pad1;
+};
+
+struct MoeRouteArgs {
+    const int* topk_ids;          // [P] = [Ttok * topk]
+    int P, topk, E;
+    int* counts;                  // [E] scratch
+    int* seg_off;                 // [E + 1] out
+    int* sorted_token;            // [P] out
+    // tile table
+    int bm, tiles_n, rows_per_flag, n_flags;
+    int* tile_first;              // [E + 1] scratch
+    MoeTile* tile_tab;
+    int tab_capacity;
+    int* n_tiles_dev;
+};
+hipError_t launch_moe_route(const MoeRouteArgs& a, hipStream_t stream);
+hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream_t stream);
 
 enum TileConfig { TILE_256x224 = 0, TILE_128x128 = 1, TILE_CONFIGS };
 
@@ -105,6 +133,11 @@ struct agg_ctx {
     int device;
     int tile_config;     // -1 = automatic
     hipStream_t producer_stream, consumer_stream;
+    // grouped GEMM workspace (grown on demand by ag_moe_gemm)
+    int* moe_ws;          // counts[E] | tile_first[E+1] | n_tiles
+    int moe_ws_ints;
+    agg::MoeTile* moe_tab;
+    int moe_tab_cap;
     int can_wait_value;  // the device supports stream waits on a memory word
     hipEvent_t gemm_done; // GEMM-RS: orders the reducer after the GEMM where it does not
 };

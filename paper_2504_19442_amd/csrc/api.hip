@@ -139,6 +139,8 @@ int symm_free(agg_ctx* c)
     if (c->producer_stream) (void)hipStreamDestroy(c->producer_stream);
     if (c->consumer_stream) (void)hipStreamDestroy(c->consumer_stream);
     if (c->gemm_done) (void)hipEventDestroy(c->gemm_done);
+    if (c->moe_ws) (void)hipFree(c->moe_ws);
+    if (c->moe_tab) (void)hipFree(c->moe_tab);
     if (c->staging) (void)hipFree(c->staging);
     if (c->signals) (void)hipFree(c->signals);
     if (c->counters) (void)hipFree(c->counters);
@@ -423,10 +425,96 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
     return rs_reduce(c, Ms, N, slots, R, ldr, r_dtype, 0, reduce_stream);
 }
 
-int ag_moe_gemm(agg_ctx*, int, int, int, int, int, const int32_t*, const void*, int32_t*, int32_t*, void*, int, int,
-                void*)
+int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* weights,
+                int32_t* sorted_token, int32_t* sorted_expert_offsets, void* Y, int ldy, int y_dtype, void* stream)
 {
-    return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (!c || Ttok < 0 || topk < 1 || E < 1 || E > 65535 || N < 0 || K < 0) return AGG_ERR_INVALID_ARG;
+    if (y_dtype != AGG_BF16 && y_dtype != AGG_F32) return AGG_ERR_INVALID_ARG;
+    if (topk > E) return AGG_ERR_INVALID_ARG;
+    if (Ttok == 0 || N == 0) return AGG_OK;
+    if (!topk_ids || !weights || !sorted_token || !sorted_expert_offsets || !Y) return AGG_ERR_INVALID_ARG;
+    if (K == 0 || K % 64 != 0 || K > (1 << 21)) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (Ttok % c->W != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const int tpr = Ttok / c->W;                                  // tokens per rank = rows per shard of T
+    if ((size_t)tpr * K * 2 != c->shard_bytes) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const int cps = c->n_signals / c->W;
+    if (tpr % cps != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const long long P = (long long)Ttok * topk;
+    const unsigned long long a_bytes = (unsigned long long)Ttok * K * 2;
+    if (P > (1ll << 30) || a_bytes >= (1ull << 31)) return AGG_ERR_UNSUPPORTED_SHAPE;   // 32-bit gather offsets
+    if (ldy < N) return AGG_ERR_INVALID_ARG;
+    if (!aligned16(weights)) return AGG_ERR_MISALIGNED;
+    if (reinterpret_cast<uintptr_t>(Y) % (y_dtype == AGG_F32 ? 4 : 2) != 0) return AGG_ERR_MISALIGNED;
+
+    // Segments are ragged (about P / E rows each): the smaller tile wastes fewer rows past a segment's end.
+    const int cfg = c->tile_config >= 0 ? c->tile_config : TILE_128x128;
+    const TileShape t = tile_shape(cfg);
+    const int tiles_n = (N + t.bn - 1) / t.bn;
+    const long long cap = (P / t.bm + E) * tiles_n;              // sum over experts of ceil(rows / bm) <= P / bm + E
+    if (cap > (1ll << 28)) return AGG_ERR_UNSUPPORTED_SHAPE;
+    // workspace of the context, grown on demand (the only calls that allocate; they synchronise the device)
+    const int ws_ints = 2 * E + 2 + 32;
+    if (c->moe_ws_ints < ws_ints) {
+        HIP_TRY(hipDeviceSynchronize());
+        if (c->moe_ws) (void)hipFree(c->moe_ws);
+        c->moe_ws = nullptr;
+        c->moe_ws_ints = 0;
+        HIP_TRY(hipMalloc((void**)&c->moe_ws, (size_t)ws_ints * sizeof(int)));
+        c->moe_ws_ints = ws_ints;
+    }
+    if (c->moe_tab_cap < cap) {
+        HIP_TRY(hipDeviceSynchronize());
+        if (c->moe_tab) (void)hipFree(c->moe_tab);
+        c->moe_tab = nullptr;
+        c->moe_tab_cap = 0;
+        HIP_TRY(hipMalloc((void**)&c->moe_tab, (size_t)cap * sizeof(MoeTile)));
+        c->moe_tab_cap = (int)cap;
+    }
+    MoeRouteArgs r{};
+    r.topk_ids = topk_ids;
+    r.P = (int)P;
+    r.topk = topk;
+    r.E = E;
+    r.counts = c->moe_ws;
+    r.tile_first = c->moe_ws + E;
+    r.n_tiles_dev = c->moe_ws + 2 * E + 1 + 16;
+    r.seg_off = sorted_expert_offsets;
+    r.sorted_token = sorted_token;
+    r.bm = t.bm;
+    r.tiles_n = tiles_n;
+    r.rows_per_flag = tpr / cps;
+    r.n_flags = c->n_signals;
+    r.tile_tab = c->moe_tab;
+    r.tab_capacity = (int)cap;
+    int rc = hip_fail(launch_moe_route(r, (hipStream_t)stream));
+    if (rc != AGG_OK) return rc;
+
+    GemmParams p{};
+    p.A = (const uint16_t*)c->staging;
+    p.B = (const uint16_t*)weights;
+    p.C = Y;
+    p.lda = K;
+    p.ldb = K;
+    p.ldc = ldy;
+    p.M = (int)P;
+    p.N = N;
+    p.K = K;
+    p.c_is_f32 = y_dtype == AGG_F32;
+    p.c_vec_ok = aligned16(Y) && ((long long)ldy * (p.c_is_f32 ? 4 : 2)) % 16 == 0;
+    p.tiles_n = tiles_n;
+    p.flags = c->signals;
+    p.epoch = c->epoch;
+    p.n_flags = c->n_signals;
+    p.rows_per_flag = r.rows_per_flag;
+    p.wait_ticks = wait_ticks(c);
+    p.err = c->err;
+    p.row_index = sorted_token;
+    p.tile_tab = c->moe_tab;
+    p.n_tiles_dev = r.n_tiles_dev;
+    p.b_group_stride = (long long)N * K;
+    p.a_bytes = (unsigned)a_bytes;
+    const int grid = (int)(cap < c->num_cus ? cap : c->num_cus);
+    return hip_fail(launch_gemm_grouped(p, cfg, grid, (hipStream_t)stream));
 }
 
 const char* agg_strerror(int code)

@@ -121,7 +121,10 @@ struct Cfg {
 };
 
 // Register budget: 448 of the 512 registers a SIMD has (see the file comment).
-template <int BM, int BN>
+// GROUPED = the MoE grouped GEMM (Section 4.1): tiles come from a table built on the device, rows of A are gathered
+// through row_index, B is the tile's expert's matrix, and rows at or past the tile's segment end are neither loaded
+// (they read as zero) nor stored.
+template <int BM, int BN, bool GROUPED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gemm_kernel(const GemmParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)    // the body names gfx950 registers; the host pass only needs the launch stub
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
         fr_off[h] = (lane & 31) * ROW_BYTES + (((2 * h + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
 
     const int KS = p.K / BK;             // stages
-    const int total_tiles = p.tiles_m * p.tiles_n;
+    const int total_tiles = GROUPED ? *p.n_tiles_dev : p.tiles_m * p.tiles_n;
     const int G = gridDim.x;
     const int g = blockIdx.x;
     const int xcd_slots = G >> 3;        // workgroups per XCD when G % 8 == 0
@@ -161,8 +164,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
         int t;
         if ((G & 7) == 0) t = base + (g & 7) * xcd_slots + (g >> 3); else t = base + g;
         if (t >= total_tiles) continue;
-        int m_tile, n_tile;
-        {
+        int m0, n0, m_lim, f_lo = 0, f_hi = -1, expert = 0;
+        if constexpr (GROUPED) {
+            const MoeTile mt = p.tile_tab[t];
+            expert = __builtin_amdgcn_readfirstlane(mt.expert);
+            m0 = __builtin_amdgcn_readfirstlane(mt.m0);
+            m_lim = __builtin_amdgcn_readfirstlane(mt.m_end);
+            n0 = __builtin_amdgcn_readfirstlane(mt.n_tile) * BN;
+            f_lo = __builtin_amdgcn_readfirstlane(mt.f_lo);
+            f_hi = __builtin_amdgcn_readfirstlane(mt.f_hi);
+        } else {
+            int m_tile, n_tile;
             const int per_panel = p.panel_m * p.tiles_n;
             const int panel = t / per_panel;
             const int pm = min(p.panel_m, p.tiles_m - panel * p.panel_m);
@@ -173,13 +185,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             const int mi = r / gn;
             n_tile = blk * p.group_n + (r - mi * gn);
             m_tile = (p.m_tile_start + panel * p.panel_m + mi) % p.tiles_m;
+            m0 = m_tile * BM;
+            n0 = n_tile * BN;
+            m_lim = p.M;
+            if (p.flags) {
+                f_lo = m0 / p.rows_per_flag;
+                f_hi = min((min(m0 + BM, p.M) - 1) / p.rows_per_flag, p.n_flags - 1);
+            }
         }
-        const int m0 = m_tile * BM, n0 = n_tile * BN;
 
         // ---- wait for the signals covering rows [m0, min(m0+BM, M))  (wait + consume_token, Section 2.2)
         if (p.flags) {
-            const int f_lo = m0 / p.rows_per_flag;
-            const int f_hi = min((min(m0 + BM, p.M) - 1) / p.rows_per_flag, p.n_flags - 1);
             int gave_up = 0;
             for (int f = f_lo + tid; f <= f_hi; f += 256) {
                 const int* fp = p.flags + (long long)f * kSignalStride;
@@ -206,18 +222,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
         // ---- per-tile buffer descriptors and per-lane load offsets (bytes from the tile's A / B origin);
         // rows past the edge of the matrix fall outside the descriptor and load as zero
         const __amdgpu_buffer_rsrc_t a_rsrc =
-            make_rsrc(p.A + (long long)m0 * p.lda, (unsigned)(min(BM, p.M - m0) * (int)p.lda * 2));
+            GROUPED ? make_rsrc(p.A, p.a_bytes)
+                    : make_rsrc(p.A + (long long)m0 * p.lda, (unsigned)(min(BM, p.M - m0) * (int)p.lda * 2));
         const __amdgpu_buffer_rsrc_t b_rsrc =
-            make_rsrc(p.B + (long long)n0 * p.ldb, (unsigned)(min(BN, p.N - n0) * (int)p.ldb * 2));
+            make_rsrc(p.B + (GROUPED ? (long long)expert * p.b_group_stride : 0ll) + (long long)n0 * p.ldb,
+                      (unsigned)(min(BN, p.N - n0) * (int)p.ldb * 2));
         // unit i of this wave is unit u = wave + 4i of the stage: A units first, then B units
         unsigned ld_off[L];
 #pragma unroll
         for (int i = 0; i < L; ++i) {
             const int u = wave + 4 * i;
             const int chunk = (u & 1) ? ld_chunk_odd : ld_chunk_even;
-            if (4 * i < C_::A_UNITS)
-                ld_off[i] = (unsigned)((u * UNIT_ROWS + ld_row) * (int)p.lda * 2 + chunk * 16);
-            else
+            if (4 * i < C_::A_UNITS) {
+                if constexpr (GROUPED) {
+                    // gathered row: the token of output row m0 + r; rows past the segment end get an offset outside
+                    // the descriptor and load as zero
+                    const int row = m0 + u * UNIT_ROWS + ld_row;
+                    const int tok = row < m_lim ? p.row_index[row] : -1;
+                    ld_off[i] = tok >= 0 ? (unsigned)tok * (unsigned)(p.lda * 2) + (unsigned)(chunk * 16) : 0xFFFFFF00u;
+                } else {
+                    ld_off[i] = (unsigned)((u * UNIT_ROWS + ld_row) * (int)p.lda * 2 + chunk * 16);
+                }
+            } else
                 ld_off[i] = (unsigned)(((u - C_::A_UNITS) * UNIT_ROWS + ld_row) * (int)p.ldb * 2 + chunk * 16);
         }
 
@@ -345,7 +371,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             const bool fast = p.c_vec_ok && n0 + BN <= p.N;
             // where a row of the output goes: C, or (GEMM-RS) this rank's own slot; nullptr = not stored
             auto row_ptr = [&](int row, int esz) -> char* {
-                if (row >= p.M) return nullptr;
+                if (row >= m_lim) return nullptr;
                 if (p.C_own && row >= p.own_lo && row < p.own_hi)
                     return (char*)p.C_own + ((long long)(row - p.own_lo) * p.ldc_own + n0) * esz;
                 return p.C ? (char*)p.C + ((long long)row * p.ldc + n0) * esz : nullptr;
@@ -383,7 +409,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                         char* base = own_all ? (char*)p.C_own + ((long long)(row0 - p.own_lo) * p.ldc_own + n0) * esz
                                              : (p.C ? (char*)p.C + ((long long)row0 * p.ldc + n0) * esz : nullptr);
                         const unsigned ld_bytes = (unsigned)((own_all ? p.ldc_own : p.ldc) * esz);
-                        const int rows_ok = min(32, p.M - row0);
+                        const int rows_ok = min(32, m_lim - row0);
                         constexpr int GRP = 7;
                         int r = r_lane, cc = cc_lane;
                         static_for<(iters + GRP - 1) / GRP>([&](auto g_c) {
@@ -464,26 +490,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 #endif
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool GROUPED>
 static hipError_t launch_cfg(const GemmParams& p, int grid, hipStream_t stream)
 {
     using C_ = Cfg<BM, BN>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<BM, BN>,
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<BM, BN, GROUPED>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C_::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<BM, BN>), dim3(grid), dim3(256), C_::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, GROUPED>), dim3(grid), dim3(256), C_::LDS_BYTES, stream, p);
     return hipGetLastError();
 }
 
 hipError_t launch_gemm(const GemmParams& p, int cfg, int grid, hipStream_t stream)
 {
     switch (cfg) {
-        case TILE_256x224: return launch_cfg<256, 224>(p, grid, stream);
-        default: return launch_cfg<128, 128>(p, grid, stream);
+        case TILE_256x224: return launch_cfg<256, 224, false>(p, grid, stream);
+        default: return launch_cfg<128, 128, false>(p, grid, stream);
+    }
+}
+
+hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream_t stream)
+{
+    switch (cfg) {
+        case TILE_256x224: return launch_cfg<256, 224, true>(p, grid, stream);
+        default: return launch_cfg<128, 128, true>(p, grid, stream);
     }
 }
 
