@@ -213,6 +213,63 @@ def main() -> int:
                           "achieved_GBps": round(rs.reducer_bytes / t_red / 1e9, 1),
                           "frac_of_hbm_peak": round(rs.reducer_bytes / t_red / 1e9 / PEAK_HBM_GBPS, 4)}
 
+        # GEMM + ReduceScatter at its full size: one GEMM launch (own slice first) with the reducer beside it;
+        # the peers' slots are signalled before the launch (values drawn on the device, same distributions)
+        gen = torch.Generator(device="cuda").manual_seed(4000)
+        A_loc = (torch.rand((rs.M, rs.Kl), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
+        B_loc = (torch.randn((rs.N, rs.Kl), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+        P_other = torch.empty((rs.M, rs.N), device="cuda", dtype=torch.float32)
+        gctx = agg.symm_alloc(rs.W, 0, 16, rs.W)
+        gp, gc = gctx.streams()
+
+        def step_gemm_rs():
+            agg.signal_reset(gctx)
+            for w in range(1, rs.W):
+                agg.signal_set(gctx, w, gp)
+            agg.gemm_rs(gctx, rs.M, rs.N, rs.Kl, A_loc, rs.Kl, B_loc, rs.Kl, agg.B_NK, slots, P_other, R, rs.N,
+                        agg.F32, gp, gc)
+
+        t_grs = timed(step_gemm_rs, 20, 3)
+        assert agg.agg_status(gctx) == agg.OK
+        gctx.free()
+        out["gemm_rs"] = {"workload": rs.name, "ms": round(t_grs * 1e3, 4),
+                          "gemm_tflops": round(2.0 * rs.M * rs.N * rs.Kl / t_grs / 1e12, 1),
+                          "note": "GEMM (fp32 out, 8192x8192x3584) + reducer on a second stream, per step"}
+        del A_loc, B_loc, P_other, slots, R
+
+        # MoE AllGather grouped GEMM at the Table 4 shape: routing + gated grouped GEMM, producer beside it
+        ms = wl.MOE_FULL
+        Xs = [(torch.rand((ms.tokens_per_rank, ms.K), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
+              for _ in range(ms.W)]
+        Wt = (torch.randn((ms.E, ms.N, ms.K), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+        keys = torch.rand((ms.T, ms.E), device="cuda", generator=gen)
+        ids = keys.argsort(dim=1)[:, : ms.topk].to(torch.int32).contiguous()
+        mctx = agg.symm_alloc(ms.W, 0, ms.tokens_per_rank * ms.K * 2, ms.W * args.chunks)
+        mp, mc = mctx.streams()
+        mps, mcs = torch.cuda.ExternalStream(mp), torch.cuda.ExternalStream(mc)
+        Pm = ms.T * ms.topk
+        Ym = torch.empty((Pm, ms.N), device="cuda", dtype=torch.bfloat16)
+        tok = torch.empty((Pm,), device="cuda", dtype=torch.int32)
+        seg = torch.empty((ms.E + 1,), device="cuda", dtype=torch.int32)
+        ev_m = torch.cuda.Event()
+        ev_m.record(mcs)
+
+        def step_moe():
+            agg.signal_reset(mctx)
+            mps.wait_event(ev_m)
+            agg.ag_producer_emulate(mctx, Xs, None, agg.PRODUCER_KERNEL, 0, mp)
+            agg.ag_moe_gemm(mctx, ms.T, ms.topk, ms.E, ms.N, ms.K, ids, Wt, tok, seg, Ym, ms.N, agg.BF16, mc)
+            ev_m.record(mcs)
+
+        t_moe = timed(step_moe, 20, 3)
+        assert agg.agg_status(mctx) == agg.OK
+        mctx.free()
+        moe_bytes = Wt.numel() * 2 + ms.T * ms.K * 2 + Pm * ms.N * 2
+        out["moe"] = {"workload": ms.name, "ms": round(t_moe * 1e3, 4), "tflops": round(ms.flops / t_moe / 1e12, 1),
+                      "algorithmic_GBps": round(moe_bytes / t_moe / 1e9, 1),
+                      "note": "routing + signal-gated grouped GEMM with the emulated gather beside it, per step"}
+        del Xs, Wt, Ym
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of rows of the same workload
     if args.cpu_rows > 0:
         import oracle

@@ -11,7 +11,7 @@
 // Main loop: K is cut into stages of 64, so that every row of a tile is fetched as one whole 128-byte line
 // (the L2 hands out lines: asking for half a line at a time halves its useful bandwidth, and the loop was
 // bound by exactly that).  A and B tiles go from global memory straight into LDS (buffer_load_dwordx4 ... lds,
-// 16 bytes per lane) into one of two stage buffers.  Rows are 128 bytes in LDS; the 16-byte chunk c of row r
+// 16 bytes per lane) into a ring that takes up nearly all of the LDS (two stages and a third of a third one).  Rows are 128 bytes in LDS; the 16-byte chunk c of row r
 // sits in slot c ^ ((r >> 1) & 7), which makes the ds_read_b128 operand fetches bank-conflict free.  Each
 // wave owns BM/4 rows and all BN columns of the tile and feeds v_mfma_f32_32x32x16_bf16; a stage is four
 // quarter-steps of K=16, and the fragments of a quarter-step are read from LDS while the previous one is on
@@ -30,6 +30,7 @@
 // SIMD: communication and computation share all CUs instead of splitting them (Section 3.8).
 #include "agg_internal.h"
 
+#include <numeric>
 #include <type_traits>
 #include <utility>
 
@@ -100,13 +101,23 @@ struct Cfg {
     static constexpr int UNITS = A_UNITS + B_UNITS;
     static constexpr int L = UNITS / 4;          // load instructions per wave per stage
     static constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+    // The LDS ring holds RW loads per wave (4 KiB each: the same load of all four waves), a stage is L of them.
+    // RW >= 2 L; RW need not be a multiple of L: the stream of loads simply wraps around the ring, so that the
+    // whole LDS is used as look-ahead even when only 2 1/3 stages fit.
+#ifndef AGG_RING_BIG
+#define AGG_RING_BIG 35
+#endif
+    static constexpr int RW = (BM == 256) ? AGG_RING_BIG : 32;
+    static constexpr int RING_BYTES = RW * 4096;
+    static constexpr int PERIOD = std::lcm(L, RW) / L;     // stages after which ring positions repeat
     // epilogue staging: each wave stages 32 rows x BN columns at a time
     static constexpr int PITCH_BF16 = BN * 2 + 16;
     static constexpr int PITCH_F32 = BN * 4 + 16;
-    static constexpr int LDS_BYTES = (2 * STAGE_BYTES > 4 * 32 * PITCH_F32) ? 2 * STAGE_BYTES : 4 * 32 * PITCH_F32;
+    static constexpr int LDS_BYTES = (RING_BYTES > 4 * 32 * PITCH_F32) ? RING_BYTES : 4 * 32 * PITCH_F32;
     static_assert(BM % 128 == 0 && BN % 32 == 0, "tile shape");
     static_assert(A_UNITS % 4 == 0 && B_UNITS % 4 == 0, "units must split evenly over 4 waves");
-    static_assert(L <= 63, "vmcnt range");
+    static_assert(RW >= 2 * L && RW <= 63, "ring: at least two stages, and the prologue's loads fit the vmcnt range");
+    static_assert(PERIOD <= 8, "the main loop is unrolled over PERIOD stages");
     static_assert(ACC == 64 || ACC == 128 || ACC == 224 || ACC == 256, "add a reservation line for this accumulator count");
     // One quarter-step is SLOTS = MB*NB MFMAs.  Its memory instructions, in order: LQ global->LDS loads
     // (while a stage's loads are being issued: the three quarter-steps after a barrier), then the F = MB+NB
@@ -247,22 +258,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                 ld_off[i] = (unsigned)(((u - C_::A_UNITS) * UNIT_ROWS + ld_row) * (int)p.ldb * 2 + chunk * 16);
         }
 
-        // one global->LDS load (unit i of this wave) of stage ks into buffer buf
-        auto load_unit = [&](int i, int buf, int ks) {
-            const int u = wave + 4 * i;
-            const bool is_a = 4 * i < C_::A_UNITS;      // the same for all four waves
-            unsigned char* dst = lds + buf * C_::STAGE_BYTES + u * 1024;
+        // one global->LDS load: the i-th load of stage ks of this wave, into ring position pos (compile-time)
+        auto load_unit = [&](auto i_c, auto pos_c, int ks) {
+            constexpr int i = decltype(i_c)::value, pos = decltype(pos_c)::value;
+            constexpr bool is_a = 4 * i < C_::A_UNITS;      // the same for all four waves
+            unsigned char* dst = lds + pos * 4096 + wave * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
                                                      ks * ROW_BYTES, 0, 0);
         };
 
         // two fragment sets, one per parity of the quarter-step.  Fragment f < MB is the A fragment of row
-        // block f, fragment MB + j the B fragment of column block j.
+        // block f, fragment MB + j the B fragment of column block j.  The 32 rows of a fragment are the k-th
+        // load of the stage (of all four waves), at ring position (base + k) mod RW, base = stage * L mod RW.
         bf16x8 fr[2][MB + NB];
-        auto read_frag = [&](int f, int buf, int h, int set) {
-            const unsigned char* src = lds + buf * C_::STAGE_BYTES + fr_off[h] +
-                                       (f < MB ? (wave * TM + f * 32) * ROW_BYTES : (BM + (f - MB) * 32) * ROW_BYTES);
-            fr[set][f] = *(const bf16x8*)src;
+        auto read_frag = [&](auto f_c, auto base_c, int h, int set) {
+            constexpr int f = decltype(f_c)::value, base = decltype(base_c)::value;
+            int pos;
+            if constexpr (f < MB) {
+                pos = base + wave * MB + f;                  // wave-uniform
+                if (pos >= C_::RW) pos -= C_::RW;
+            } else {
+                pos = (base + C_::A_UNITS / 4 + (f - MB)) % C_::RW;
+            }
+            fr[set][f] = *(const bf16x8*)(lds + pos * 4096 + fr_off[h]);
         };
 
 #ifdef AGG_EXP_TIMING
@@ -270,16 +288,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 #endif
         static_for<C_::ACC>([&](auto r) { acc_zero<decltype(r)::value>(); });
 
-        // ---- prologue: both stage buffers in flight (a stage past the end re-loads the last one: harmless,
-        // and it keeps the number of outstanding loads per wave the same on every path)
-#pragma unroll
-        for (int i = 0; i < L; ++i) load_unit(i, 0, 0);
-#pragma unroll
-        for (int i = 0; i < L; ++i) load_unit(i, 1, min(1, KS - 1));
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(L));
+        // ---- prologue: the first RW - L + LQ loads of the stream (stage 0, stage 1, the head of stage 2 ...);
+        // the main loop's first quarter-steps continue the stream from there.  A stage past the end re-loads
+        // the last one: harmless, and it keeps the count of outstanding loads the same on every path.
+        constexpr int RW = C_::RW, PERIOD = C_::PERIOD, LQ = C_::LQ;
+        static_for<RW - L + LQ>([&](auto n_c) {
+            constexpr int n = decltype(n_c)::value;
+            load_unit(std::integral_constant<int, n % L>{}, std::integral_constant<int, n % RW>{}, min(n / L, KS - 1));
+        });
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(RW - 2 * L + LQ));     // stage 0 has landed
         __builtin_amdgcn_s_barrier();
-#pragma unroll
-        for (int f = 0; f < MB + NB; ++f) read_frag(f, 0, 0, 0);
+        static_for<MB + NB>([&](auto f_c) { read_frag(f_c, std::integral_constant<int, 0>{}, 0, 0); });
 
         // experiment switches (never defined in the product build): drop work from the main loop to see what it costs
 #ifdef AGG_EXP_NO_LDSREAD
@@ -295,23 +314,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 #ifdef AGG_EXP_TIMING
         const long long tt1 = __builtin_readcyclecounter();
 #endif
-        // ---- main loop, two stages per pass so that buffer indices are constants.  The MFMAs are volatile
+        // ---- main loop, PERIOD stages per pass so that ring positions are constants.  The MFMAs are volatile
         // asm, so memory operations keep their place between them: the order below is the schedule.  Slot q of
         // a quarter-step works on column block q / MB, row block q % MB; the B fragment is the first MFMA
         // operand, so accumulator block (i, j) holds the transposed 32x32 block.
         //
-        // Stage ks in buffer b: quarter-steps 0..2 read ahead inside b; then every wave waits for its loads of
-        // stage ks+1 and meets at the barrier -- all of stage ks+1 is in LDS and nobody needs buffer b any
-        // more; quarter-step 3 reads the first fragments of stage ks+1 from the other buffer.  The loads of
-        // stage ks+2 go into b, LOAD_SLOTS per quarter-step, starting right after the barrier.
-        for (int ks0 = 0;; ks0 += 2) {
+        // Stage ks: quarter-steps 0..2 read ahead inside the stage; then every wave waits until its loads of
+        // stage ks+1 have landed (RW - 2L younger ones may still be in flight) and meets the others at the
+        // barrier -- all of stage ks+1 is in LDS and nobody needs stage ks any more; quarter-step 3 reads the
+        // first fragments of stage ks+1.  Each barrier releases the L ring positions of stage ks: the next L
+        // loads of the stream (load n goes where load n - RW was, and n - RW is a load of stage ks) are issued
+        // LQ per quarter-step over the next three quarter-steps.  They belong to stages ks+2 and later, so each
+        // has at least a whole stage of MFMA work to land.
+        for (int ks0 = 0;; ks0 += PERIOD) {
             bool done = false;
-            static_for<2>([&](auto b_c) {
-                constexpr int b = decltype(b_c)::value;
+            static_for<PERIOD>([&](auto ph_c) {
+                constexpr int ph = decltype(ph_c)::value;
                 if (done) return;
-                const int ks = ks0 + b;
-                const int ks_load_prev = min(ks + 1, KS - 1);     // the batch begun in the previous stage's last quarter
-                const int ks_load = min(ks + 2, KS - 1);
+                const int ks = ks0 + ph;
+                constexpr int base_cur = (ph * L) % RW;                          // ring base of stage ks
+                constexpr int base_next = ((ph + 1) * L) % RW;                   // of stage ks+1
+                constexpr int base_prev = (((ph + PERIOD - 1) % PERIOD) * L) % RW;   // of stage ks-1
                 static_for<QS>([&](auto h_c) {
                     constexpr int h = decltype(h_c)::value;
                     constexpr int set = h & 1;
@@ -323,29 +346,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                             if constexpr (h == QS - 2) {
                                 // the quarter before the barrier issues no loads: its fragment reads go first, so
                                 // that they are back when the wave reaches the barrier
-                                if constexpr (o < C_::F) LOOP_READ_FRAG(o, b, h + 1, 1 - set);
-                            } else if constexpr (o < C_::LQ) {
-                                // quarter 3 starts the batch for stage ks+2 (into this buffer, free since the
-                                // barrier); quarters 0 and 1 finish the batch for stage ks+1 begun in the
-                                // previous stage's last quarter
+                                if constexpr (o < C_::F)
+                                    LOOP_READ_FRAG(std::integral_constant<int, o>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
+                            } else if constexpr (o < LQ) {
+                                // quarter 3 starts the batch released by this stage's barrier (j-th load of the
+                                // batch: stream index ks*L + RW + j); quarters 0 and 1 finish the batch released by
+                                // the previous stage's barrier
                                 if constexpr (h == QS - 1) {
-                                    if constexpr (o < L) LOOP_LOAD_UNIT(o, b, ks_load);
+                                    constexpr int j = o;
+                                    if constexpr (j < L)
+                                        LOOP_LOAD_UNIT(std::integral_constant<int, (RW + j) % L>{},
+                                                       std::integral_constant<int, (base_cur + j) % RW>{},
+                                                       min(ks + (RW + j) / L, KS - 1));
                                 } else {
-                                    constexpr int i = (h + 1) * C_::LQ + o;
-                                    if constexpr (i < L) LOOP_LOAD_UNIT(i, 1 - b, ks_load_prev);
+                                    constexpr int j = (h + 1) * LQ + o;
+                                    if constexpr (j < L)
+                                        LOOP_LOAD_UNIT(std::integral_constant<int, (RW + j) % L>{},
+                                                       std::integral_constant<int, (base_prev + j) % RW>{},
+                                                       min(ks - 1 + (RW + j) / L, KS - 1));
                                 }
-                            } else if constexpr (o - C_::LQ < C_::F) {
-                                constexpr int f = o - C_::LQ;
-                                if constexpr (h < QS - 1) LOOP_READ_FRAG(f, b, h + 1, 1 - set);
-                                else LOOP_READ_FRAG(f, 1 - b, 0, 1 - set);
+                            } else if constexpr (o - LQ < C_::F) {
+                                constexpr int f = o - LQ;
+                                if constexpr (h < QS - 1)
+                                    LOOP_READ_FRAG(std::integral_constant<int, f>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
+                                else
+                                    LOOP_READ_FRAG(std::integral_constant<int, f>{}, std::integral_constant<int, base_next>{}, 0, 1 - set);
                             }
                         });
                     });
                     if constexpr (h == QS - 2) {
 #ifndef AGG_EXP_NO_BARRIER
-                        // stage ks+1 has landed for this wave, its own fragment reads of this stage are back;
-                        // after the barrier that holds for all waves
-                        __builtin_amdgcn_s_waitcnt(0);      // vmcnt(0) expcnt(0) lgkmcnt(0)
+                        // stage ks+1 has landed for this wave (all but the RW - 2L youngest loads are back), its own
+                        // fragment reads of this stage are back; after the barrier that holds for all waves
+                        __builtin_amdgcn_s_waitcnt(vmcnt_imm(RW - 2 * L) & ~(0xF << 8));     // and lgkmcnt(0)
                         __builtin_amdgcn_s_barrier();
 #endif
                     }
