@@ -33,6 +33,49 @@ def _measured_traffic(workload: str):
     return None
 
 
+class HipEvents:
+    """HIP events made without the system-scope fence that a default event adds when it completes (that fence
+    flushes and invalidates the L2 between the kernels it sits between, which would be charged to the kernels
+    being timed).  Plumbing for the measurement only."""
+
+    def __init__(self):
+        import ctypes
+        self.C = ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.live = []
+
+    def new(self, timing: bool = True):
+        ev = self.C.c_void_p()
+        flags = 0x20000000 | (0 if timing else 0x2)      # hipEventDisableSystemFence | hipEventDisableTiming
+        rc = self.hip.hipEventCreateWithFlags(self.C.byref(ev), self.C.c_uint(flags))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreateWithFlags failed ({rc})")
+        self.live.append(ev)
+        return ev
+
+    def record(self, ev, stream: int):
+        rc = self.hip.hipEventRecord(ev, self.C.c_void_p(stream))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed ({rc})")
+
+    def wait(self, stream: int, ev):
+        rc = self.hip.hipStreamWaitEvent(self.C.c_void_p(stream), ev, self.C.c_uint(0))
+        if rc != 0:
+            raise RuntimeError(f"hipStreamWaitEvent failed ({rc})")
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = self.C.c_float()
+        rc = self.hip.hipEventElapsedTime(self.C.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def close(self):
+        for ev in self.live:
+            self.hip.hipEventDestroy(ev)
+        self.live = []
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,20 +119,24 @@ def main() -> int:
     M, N, K = shape.M, shape.N, shape.K
     C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
     prod, cons = run.prod, run.cons
-    ev_cons_done = torch.cuda.Event()
+    prod_h, cons_h = prod.cuda_stream, cons.cuda_stream
+    hev = HipEvents()
+    ev_cons_done = hev.new(timing=False)
 
     def step_fused(ev_pairs=None):
         agg.signal_reset(ctx)
-        prod.wait_event(ev_cons_done)          # T is shared: the next arrival waits for the last consumer
+        hev.wait(prod_h, ev_cons_done)         # T is shared: the next arrival waits for the last consumer
         agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, prod)
         if ev_pairs is not None:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(cons)
+            e0, e1 = ev_pairs[step_fused.k]
+            step_fused.k += 1
+            hev.record(e0, cons_h)
         agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
         if ev_pairs is not None:
-            e1.record(cons)
-            ev_pairs.append((e0, e1))
-        ev_cons_done.record(cons)
+            hev.record(e1, cons_h)
+        hev.record(ev_cons_done, cons_h)
+
+    step_fused.k = 0
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -121,19 +168,19 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    ev_cons_done.record(cons)
+    hev.record(ev_cons_done, cons_h)
     # ---- the headline: fused step
     for _ in range(args.warmup):
         step_fused()
     torch.cuda.synchronize()
-    pairs = []
+    pairs = [(hev.new(), hev.new()) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step_fused(pairs)
     torch.cuda.synchronize()
     t_fused = (time.perf_counter() - t0) / args.steps
     assert agg.agg_status(ctx) == agg.OK, "a wait timed out during the bench"
-    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+    kern_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in pairs]))
     flops = shape.flops
     tflops = flops / t_fused / 1e12
 
@@ -173,7 +220,7 @@ def main() -> int:
         n2, rounds = max(5, args.steps // 5), 5
         acc = {"fused": [], "gemm": [], "copy": [], "serial": []}
         for _ in range(rounds):
-            ev_cons_done.record(cons)
+            hev.record(ev_cons_done, cons_h)
             acc["fused"].append(timed(step_fused_plain, n2, 2))
             agg.signal_reset(ctx)
             step_copy()
@@ -251,15 +298,15 @@ def main() -> int:
         Ym = torch.empty((Pm, ms.N), device="cuda", dtype=torch.bfloat16)
         tok = torch.empty((Pm,), device="cuda", dtype=torch.int32)
         seg = torch.empty((ms.E + 1,), device="cuda", dtype=torch.int32)
-        ev_m = torch.cuda.Event()
-        ev_m.record(mcs)
+        ev_m = hev.new(timing=False)
+        hev.record(ev_m, mc)
 
         def step_moe():
             agg.signal_reset(mctx)
-            mps.wait_event(ev_m)
+            hev.wait(mp, ev_m)
             agg.ag_producer_emulate(mctx, Xs, None, agg.PRODUCER_KERNEL, 0, mp)
             agg.ag_moe_gemm(mctx, ms.T, ms.topk, ms.E, ms.N, ms.K, ids, Wt, tok, seg, Ym, ms.N, agg.BF16, mc)
-            ev_m.record(mcs)
+            hev.record(ev_m, mc)
 
         t_moe = timed(step_moe, 20, 3)
         assert agg.agg_status(mctx) == agg.OK
@@ -284,6 +331,7 @@ def main() -> int:
                                "cores": oracle.threads(), "kind": "oracle",
                                "sample": f"{len(rows)} evenly spaced rows of C (all {N} columns), {dt:.2f} s",
                                "gpu_matches_oracle_on_sample": ok}
+    hev.close()
     run.close()
     print(json.dumps(out), flush=True)
     return 0

@@ -147,6 +147,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
     else if constexpr (C_::ACC == 128) asm volatile("; accumulators a0..a127" ::: "a127");
     else asm volatile("; accumulators a0..a63" ::: "a63");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+#ifdef AGG_EXP_PRIO
+    __builtin_amdgcn_s_setprio(AGG_EXP_PRIO);
+#endif
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -170,6 +173,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
     const int g = blockIdx.x;
     const int xcd_slots = G >> 3;        // workgroups per XCD when G % 8 == 0
 
+#ifdef AGG_EXP_STAGGER
+    for (int d = 0; d < (g & 7) * AGG_EXP_STAGGER; ++d) __builtin_amdgcn_s_sleep(16);
+#endif
     for (int base = 0; base < total_tiles; base += G) {
         // ---- which tile: consecutive tiles of the list go to the workgroups of one XCD
         int t;
@@ -397,6 +403,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
         asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7");     // the last MFMAs retire before the read-out
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));              // the last (redundant) loads have landed in LDS
         __syncthreads();                                       // and every wave is done with the ring
+#ifdef AGG_EXP_TIMING
+        const long long tta = __builtin_readcyclecounter();
+#endif
         {
             int lane_e = lane;
             asm volatile("" : "+v"(lane_e));     // keeps the address arithmetic below inside the tile loop
@@ -445,6 +454,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                         const int rows_ok = min(32, m_lim - row0);
                         constexpr int GRP = 7;
                         int r = r_lane, cc = cc_lane;
+                        if constexpr ((32 * cpr) % 64 == 0) {
+                            // the common case -- all 32 rows inside the matrix (or segment) and bound for one
+                            // destination -- has no per-lane conditions at all: every lane moves `iters` chunks
+                            if (base && rows_ok >= 32 && (own_all || own_none)) {
+                                static_for<(iters + GRP - 1) / GRP>([&](auto g_c) {
+                                    constexpr int it0 = decltype(g_c)::value * GRP;
+                                    constexpr int n = (iters - it0 < GRP) ? iters - it0 : GRP;
+                                    u32x4 val[n];
+                                    unsigned off[n];
+                                    static_for<n>([&](auto k_c) {
+                                        constexpr int k = decltype(k_c)::value;
+                                        off[k] = (unsigned)r * ld_bytes + (unsigned)cc * 16u;
+                                        val[k] = *(const u32x4*)(stage + r * pitch + cc * 16);
+                                        cc += 64 % cpr;
+                                        r += 64 / cpr;
+                                        const bool wrap = cc >= cpr;
+                                        cc = wrap ? cc - cpr : cc;
+                                        r = wrap ? r + 1 : r;
+                                    });
+                                    static_for<n>([&](auto k_c) {
+                                        constexpr int k = decltype(k_c)::value;
+                                        __builtin_nontemporal_store(val[k], (u32x4*)(base + off[k]));
+                                    });
+                                });
+                                return;     // next row block
+                            }
+                        }
                         static_for<(iters + GRP - 1) / GRP>([&](auto g_c) {
                             constexpr int it0 = decltype(g_c)::value * GRP;
                             constexpr int n = (iters - it0 < GRP) ? iters - it0 : GRP;
@@ -463,8 +499,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                             static_for<n>([&](auto k_c) {
                                 constexpr int k = decltype(k_c)::value;
                                 if (own_all || own_none) {
-                                    if (base && rs[k] < rows_ok)
-                                        *(u32x4*)(base + (unsigned)rs[k] * ld_bytes + (unsigned)ccs[k] * 16u) = val[k];
+                                    if (base && rs[k] < rows_ok) {
+                                        // C is not read again by this kernel: streaming stores keep it from
+                                        // displacing the A and B lines that are
+                                        __builtin_nontemporal_store(val[k], (u32x4*)(base + (unsigned)rs[k] * ld_bytes + (unsigned)ccs[k] * 16u));
+                                    }
                                 } else {
                                     char* dst = rs[k] < 32 ? row_ptr(row0 + rs[k], esz) : nullptr;
                                     if (dst) *(u32x4*)(dst + ccs[k] * 16) = val[k];
@@ -491,6 +530,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             if (p.c_is_f32) epilogue(float{}); else epilogue(__bf16{});
         }
 
+#ifdef AGG_EXP_TIMING
+        const long long ttb = __builtin_readcyclecounter();
+#endif
         // GEMM-RS: count finished tiles of the own slice; the last one raises the producer signal
         if (p.done_ctr && m0 < p.own_hi && m0 + BM > p.own_lo) {
             __builtin_amdgcn_s_waitcnt(0);   // this wave's stores of the tile have reached L2 ...
@@ -515,6 +557,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             const long long tt3 = __builtin_readcyclecounter();
             long long* dbg = (long long*)(p.err + 8) + (g ? 4 : 0);
             dbg[0] = tt1 - tt0; dbg[1] = tt2 - tt1; dbg[2] = tt3 - tt2; dbg[3] = KS;
+            if (g == 0) { dbg[8] = tta - tt2; dbg[9] = ttb - tta; dbg[10] = tt3 - ttb; }
         }
 #endif
     }
