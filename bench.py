@@ -79,8 +79,9 @@ class HipEvents:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps first; the chip needs some tens of ms under load to settle its clocks")
     ap.add_argument("--workload", default="ag_gemm_70b_mlp")
     ap.add_argument("--tile", type=int, default=-1)
     ap.add_argument("--chunks", type=int, default=4, help="signals per shard")

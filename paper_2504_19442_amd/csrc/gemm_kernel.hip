@@ -410,7 +410,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             int lane_e = lane;
             asm volatile("" : "+v"(lane_e));     // keeps the address arithmetic below inside the tile loop
             const int row_w = m0 + wave * TM;    // first output row of this wave
-            const bool fast = p.c_vec_ok && n0 + BN <= p.N;
+            const int n_valid = min(BN, p.N - n0);      // columns of this tile inside the matrix
             // where a row of the output goes: C, or (GEMM-RS) this rank's own slot; nullptr = not stored
             auto row_ptr = [&](int row, int esz) -> char* {
                 if (row >= m_lim) return nullptr;
@@ -423,6 +423,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                 constexpr int esz = sizeof(T);
                 typedef __attribute__((__vector_size__(4 * sizeof(T)))) T Tx4;
                 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+                // whole 16-byte chunks of rows can be stored when the pointers allow it and the tile's valid width is
+                // a whole number of chunks (always so for a full tile)
+                const bool fast = p.c_vec_ok && (n_valid * esz) % 16 == 0;
+                const int cpr_valid = n_valid * esz / 16;
                 if (fast) {
                     // stage 32 rows x BN columns per pass in this wave's own part of LDS, then move whole
                     // 16-byte chunks of rows to C: full cache lines per store instruction
@@ -457,7 +461,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                         if constexpr ((32 * cpr) % 64 == 0) {
                             // the common case -- all 32 rows inside the matrix (or segment) and bound for one
                             // destination -- has no per-lane conditions at all: every lane moves `iters` chunks
-                            if (base && rows_ok >= 32 && (own_all || own_none)) {
+                            if (base && rows_ok >= 32 && n_valid == BN && (own_all || own_none)) {
                                 static_for<(iters + GRP - 1) / GRP>([&](auto g_c) {
                                     constexpr int it0 = decltype(g_c)::value * GRP;
                                     constexpr int n = (iters - it0 < GRP) ? iters - it0 : GRP;
@@ -499,13 +503,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                             static_for<n>([&](auto k_c) {
                                 constexpr int k = decltype(k_c)::value;
                                 if (own_all || own_none) {
-                                    if (base && rs[k] < rows_ok) {
+                                    if (base && rs[k] < rows_ok && ccs[k] < cpr_valid) {
                                         // C is not read again by this kernel: streaming stores keep it from
                                         // displacing the A and B lines that are
                                         __builtin_nontemporal_store(val[k], (u32x4*)(base + (unsigned)rs[k] * ld_bytes + (unsigned)ccs[k] * 16u));
                                     }
                                 } else {
-                                    char* dst = rs[k] < 32 ? row_ptr(row0 + rs[k], esz) : nullptr;
+                                    char* dst = (rs[k] < 32 && ccs[k] < cpr_valid) ? row_ptr(row0 + rs[k], esz) : nullptr;
                                     if (dst) *(u32x4*)(dst + ccs[k] * 16) = val[k];
                                 }
                             });

@@ -29,7 +29,10 @@ __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
     const long long per_wg = (vec_per_chunk + team - 1) / team;
     const long long lo = j * per_wg, hi = lo + per_wg < vec_per_chunk ? lo + per_wg : vec_per_chunk;
     const int n_chunks = a.n_jobs * a.chunks_per_shard;
-    constexpr int NT = 2, WT = 1 | 16 | 2;          // cache policy bits: nt (streaming); sc0 | sc1 | nt (write-through)
+    // cache policy bits: loads nt (streaming); stores sc1 = agent scope, written through this XCD's L2 so that the
+    // consumer's XCDs find the data in memory (system scope or streaming stores were measured slightly slower
+    // beside the GEMM)
+    constexpr int NT = 2, WT = 16;
     for (int ch = t; ch < n_chunks; ch += n_teams) {
         const int job = ch / a.chunks_per_shard, c = ch - job * a.chunks_per_shard;
         const int r = a.rank_of[job];
