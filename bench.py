@@ -272,8 +272,8 @@ def main() -> int:
 
         def step_gemm_rs():
             agg.signal_reset(gctx)
-            for w in range(1, rs.W):
-                agg.signal_set(gctx, w, gp)
+            for w in range(1, rs.W):          # the peers' slots "arrive" on the reduce stream, ahead of the reducer
+                agg.signal_set(gctx, w, gc)
             agg.gemm_rs(gctx, rs.M, rs.N, rs.Kl, A_loc, rs.Kl, B_loc, rs.Kl, agg.B_NK, slots, P_other, R, rs.N,
                         agg.F32, gp, gc)
 

@@ -167,8 +167,8 @@ int gemm_rs(agg_ctx* ctx, int M, int N, int Klocal,
  * outputs the call fills (int32 [Ttok*topk] and int32 [E+1]) and then uses; the caller may read them.
  * A tile lies inside one expert's segment and waits for the signals of the rows of T between its first and its
  * last token (tokens rise inside a segment, so that range holds every token of the tile).
- * Requirements: K % 64 == 0, Ttok % W == 0, shard_bytes == (Ttok / W) * K * 2, Ttok * K * 2 < 2 GiB, weights 16-byte
- * aligned, ldy >= N.  Ids outside [0, E) are skipped: their pairs appear nowhere and
+ * Requirements: K % 64 == 0, Ttok % W == 0, shard_bytes == (Ttok / W) * K * 2, Ttok * K * 2 < 2 GiB, E <= 4096,
+ * weights and topk_ids 16-byte aligned, ldy >= N.  Ids outside [0, E) are skipped: their pairs appear nowhere and
  * sorted_expert_offsets[E] is then smaller than Ttok * topk.  Rows of Y past sorted_expert_offsets[E] are not
  * written.  Routing and GEMM run on `stream`; routing does not depend on T and runs before any signal is awaited.
  * The first call (and any call with a larger problem) allocates the context's tile table and synchronises the

@@ -56,12 +56,10 @@ struct MoeTile {
 struct MoeRouteArgs {
     const int* topk_ids;          // [P] = [Ttok * topk]
     int P, topk, E;
-    int* counts;                  // [E] scratch
     int* seg_off;                 // [E + 1] out
     int* sorted_token;            // [P] out
     // tile table
     int bm, tiles_n, rows_per_flag, n_flags;
-    int* tile_first;              // [E + 1] scratch
     MoeTile* tile_tab;
     int tab_capacity;
     int* n_tiles_dev;

@@ -428,7 +428,7 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
 int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* weights,
                 int32_t* sorted_token, int32_t* sorted_expert_offsets, void* Y, int ldy, int y_dtype, void* stream)
 {
-    if (!c || Ttok < 0 || topk < 1 || E < 1 || E > 65535 || N < 0 || K < 0) return AGG_ERR_INVALID_ARG;
+    if (!c || Ttok < 0 || topk < 1 || E < 1 || E > 4096 || N < 0 || K < 0) return AGG_ERR_INVALID_ARG;
     if (y_dtype != AGG_BF16 && y_dtype != AGG_F32) return AGG_ERR_INVALID_ARG;
     if (topk > E) return AGG_ERR_INVALID_ARG;
     if (Ttok == 0 || N == 0) return AGG_OK;
@@ -443,11 +443,27 @@ int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32
     const unsigned long long a_bytes = (unsigned long long)Ttok * K * 2;
     if (P > (1ll << 30) || a_bytes >= (1ull << 31)) return AGG_ERR_UNSUPPORTED_SHAPE;   // 32-bit gather offsets
     if (ldy < N) return AGG_ERR_INVALID_ARG;
-    if (!aligned16(weights)) return AGG_ERR_MISALIGNED;
+    if (!aligned16(weights) || !aligned16(topk_ids)) return AGG_ERR_MISALIGNED;
     if (reinterpret_cast<uintptr_t>(Y) % (y_dtype == AGG_F32 ? 4 : 2) != 0) return AGG_ERR_MISALIGNED;
 
-    // Segments are ragged (about P / E rows each): the smaller tile wastes fewer rows past a segment's end.
-    const int cfg = c->tile_config >= 0 ? c->tile_config : TILE_128x128;
+    // Tile shape: segments are ragged (about P / E rows each, a binomial spread around it).  Estimate the tiles
+    // each shape would need with segments 15 % above the mean, in waves over the CUs, times the cost of a tile
+    // (the small tile is bound by the global->LDS path: about 0.6 of the large tile's rate per flop).
+    int cfg = c->tile_config;
+    if (cfg < 0) {
+        const int cand[2] = {TILE_256x224, TILE_128x128};
+        const double eff[2] = {1.0, 0.6};
+        const double rows = 1.15 * (double)P / E;
+        double best = 1e300;
+        for (int i = 0; i < 2; ++i) {
+            const TileShape ts = tile_shape(cand[i]);
+            const long long mt = (long long)((rows + ts.bm - 1) / ts.bm);
+            const long long tiles = (long long)E * mt * ((N + ts.bn - 1) / ts.bn);
+            const long long waves = (tiles + c->num_cus - 1) / c->num_cus;
+            const double cost = (double)waves * ts.bm * ts.bn / eff[i];
+            if (cost < best) { best = cost; cfg = cand[i]; }
+        }
+    }
     const TileShape t = tile_shape(cfg);
     const int tiles_n = (N + t.bn - 1) / t.bn;
     const long long cap = (P / t.bm + E) * tiles_n;              // sum over experts of ceil(rows / bm) <= P / bm + E
@@ -475,8 +491,6 @@ int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32
     r.P = (int)P;
     r.topk = topk;
     r.E = E;
-    r.counts = c->moe_ws;
-    r.tile_first = c->moe_ws + E;
     r.n_tiles_dev = c->moe_ws + 2 * E + 1 + 16;
     r.seg_off = sorted_expert_offsets;
     r.sorted_token = sorted_token;

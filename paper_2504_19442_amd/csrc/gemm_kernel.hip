@@ -238,12 +238,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 
         // ---- per-tile buffer descriptors and per-lane load offsets (bytes from the tile's A / B origin);
         // rows past the edge of the matrix fall outside the descriptor and load as zero
+#ifdef AGG_EXP_SAMETILE      // experiment: every workgroup loads the operands of tile (0, 0): all L2 hits, no HBM traffic
+        const int m0l = 0, n0l = 0;
+#else
+        const int m0l = m0, n0l = n0;
+#endif
         const __amdgpu_buffer_rsrc_t a_rsrc =
             GROUPED ? make_rsrc(p.A, p.a_bytes)
-                    : make_rsrc(p.A + (long long)m0 * p.lda, (unsigned)(min(BM, p.M - m0) * (int)p.lda * 2));
+                    : make_rsrc(p.A + (long long)m0l * p.lda, (unsigned)(min(BM, p.M - m0l) * (int)p.lda * 2));
         const __amdgpu_buffer_rsrc_t b_rsrc =
-            make_rsrc(p.B + (GROUPED ? (long long)expert * p.b_group_stride : 0ll) + (long long)n0 * p.ldb,
-                      (unsigned)(min(BN, p.N - n0) * (int)p.ldb * 2));
+            make_rsrc(p.B + (GROUPED ? (long long)expert * p.b_group_stride : 0ll) + (long long)n0l * p.ldb,
+                      (unsigned)(min(BN, p.N - n0l) * (int)p.ldb * 2));
         // unit i of this wave is unit u = wave + 4i of the stage: A units first, then B units
         unsigned ld_off[L];
 #pragma unroll

@@ -6,71 +6,102 @@
 
 namespace agg {
 
-// Workgroup e counts the pairs routed to expert e.
-__global__ __launch_bounds__(256) void moe_count_kernel(const MoeRouteArgs a)
-{
-    const int e = blockIdx.x, tid = threadIdx.x;
-    int n = 0;
-    for (int i = tid; i < a.P; i += 256) n += (a.topk_ids[i] == e);
-    __shared__ int part[256];
-    part[tid] = n;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (tid < s) part[tid] += part[tid + s];
-        __syncthreads();
-    }
-    if (tid == 0) a.counts[e] = part[0];
-}
+constexpr int kMaxExperts = 4096;     // histogram bins held in LDS
 
-// Segment offsets and, per expert, the index of its first tile.  Tiles of an expert are listed n-tile by n-tile,
-// the m-tiles of one n-tile next to each other, so that the workgroups of one XCD (which take consecutive tiles)
-// read the same rows of that expert's weights at the same time.
-__global__ __launch_bounds__(256) void moe_prefix_kernel(const MoeRouteArgs a)
+// One kernel, one workgroup per expert.  Every workgroup builds the full histogram of the ids in LDS (counts do not
+// depend on the order of the atomic adds), takes its own segment offset and first tile index from the prefix sums,
+// then writes the tokens of its expert's pairs in (token, slot) order -- the order of the flat pair index -- and
+// the expert's tile entries.  Tiles of an expert are listed n-tile by n-tile, the m-tiles of one n-tile next to
+// each other, so that the workgroups of one XCD (which take consecutive tiles) read the same rows of that
+// expert's weights at the same time.  Workgroup 0 also writes the segment offsets and the tile count.
+__global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
 {
-    if (threadIdx.x == 0) {
+    const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    extern __shared__ int hist[];                 // [E] counts
+    __shared__ int wave_cnt[4][4];
+    __shared__ int s_seg_lo, s_first;
+    for (int i = tid; i < a.E; i += 256) hist[i] = 0;
+    __syncthreads();
+    // ---- pass 1: histogram (four ids per lane per step)
+    const int4* ids4 = (const int4*)a.topk_ids;
+    const int n4 = a.P / 4;
+    for (int i = tid; i < n4; i += 256) {
+        const int4 v = ids4[i];
+        if ((unsigned)v.x < (unsigned)a.E) atomicAdd(&hist[v.x], 1);
+        if ((unsigned)v.y < (unsigned)a.E) atomicAdd(&hist[v.y], 1);
+        if ((unsigned)v.z < (unsigned)a.E) atomicAdd(&hist[v.z], 1);
+        if ((unsigned)v.w < (unsigned)a.E) atomicAdd(&hist[v.w], 1);
+    }
+    for (int i = 4 * n4 + tid; i < a.P; i += 256) {
+        const int v = a.topk_ids[i];
+        if ((unsigned)v < (unsigned)a.E) atomicAdd(&hist[v], 1);
+    }
+    __syncthreads();
+    // ---- prefix sums over the experts before e (wave 0; E is small)
+    if (wave == 0) {
         int off = 0, tiles = 0;
-        for (int e = 0; e < a.E; ++e) {
-            a.seg_off[e] = off;
-            a.tile_first[e] = tiles;
-            const int c = a.counts[e];
+        for (int i = lane; i < e; i += 64) {
+            const int c = hist[i];
             off += c;
             tiles += ((c + a.bm - 1) / a.bm) * a.tiles_n;
         }
-        a.seg_off[a.E] = off;
-        a.tile_first[a.E] = tiles;
-        *a.n_tiles_dev = tiles <= a.tab_capacity ? tiles : 0;   // the capacity is an upper bound by construction
+        for (int sft = 32; sft > 0; sft >>= 1) {
+            off += __shfl_down(off, sft);
+            tiles += __shfl_down(tiles, sft);
+        }
+        if (lane == 0) { s_seg_lo = off; s_first = tiles; }
     }
-}
+    __syncthreads();
+    const int seg_lo = s_seg_lo, cnt = hist[e], seg_hi = seg_lo + cnt, first = s_first;
+    if (e == a.E - 1 && tid == 0) {
+        a.seg_off[a.E] = seg_hi;
+        const int total = first + ((cnt + a.bm - 1) / a.bm) * a.tiles_n;
+        *a.n_tiles_dev = total <= a.tab_capacity ? total : 0;   // the capacity is an upper bound by construction
+    }
+    if (tid == 0) a.seg_off[e] = seg_lo;
 
-// Workgroup e writes the tokens of expert e's pairs in (token, slot) order -- the order of the flat pair index --
-// then the expert's tile entries.
-__global__ __launch_bounds__(256) void moe_place_kernel(const MoeRouteArgs a)
-{
-    const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    __shared__ int wave_cnt[4];
-    const int seg_lo = a.seg_off[e], seg_hi = a.seg_off[e + 1];
+    // ---- pass 2: stable placement, 1024 pairs per step (lane handles 4 consecutive pairs)
     int running = seg_lo;
-    for (int base = 0; base < a.P; base += 256) {
-        const int i = base + tid;
-        const bool match = i < a.P && a.topk_ids[i] == e;
-        const unsigned long long bal = __ballot(match);
-        if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    for (int base = 0; base < a.P; base += 1024) {
+        const int i0 = base + 4 * tid;
+        int v[4];
+        if (i0 + 3 < a.P && (a.P & 3) == 0) {
+            const int4 q = ids4[i0 >> 2];
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = i0 + k < a.P ? a.topk_ids[i0 + k] : -1;
+        }
+        int mine = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) mine += (v[k] == e);
+        // exclusive prefix of `mine` over the workgroup, in thread order
+        int incl = mine;
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) {
+            const int t = __shfl_up(incl, sft);
+            if (lane >= sft) incl += t;
+        }
+        if (lane == 63) wave_cnt[(base >> 10) & 3][wave] = incl;
         __syncthreads();
         int before = 0, total = 0;
+#pragma unroll
         for (int w = 0; w < 4; ++w) {
-            if (w < wave) before += wave_cnt[w];
-            total += wave_cnt[w];
+            const int c = wave_cnt[(base >> 10) & 3][w];
+            if (w < wave) before += c;
+            total += c;
         }
-        if (match) a.sorted_token[running + before + __popcll(bal & ((1ull << lane) - 1ull))] = i / a.topk;
+        int pos = running + before + incl - mine;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (v[k] == e) a.sorted_token[pos++] = (i0 + k) / a.topk;
         running += total;
-        __syncthreads();
+        // wave_cnt is used round-robin over four steps, so one barrier per step is enough
     }
-    // tile entries (they read sorted_token written above by this same workgroup)
+    // ---- tile entries (they read sorted_token written above by this same workgroup)
     __threadfence_block();
     __syncthreads();
-    const int cnt = seg_hi - seg_lo;
     const int mt = (cnt + a.bm - 1) / a.bm;
-    const int first = a.tile_first[e];
     if (first + mt * a.tiles_n > a.tab_capacity) return;
     for (int k = tid; k < mt * a.tiles_n; k += 256) {
         const int n = k / mt, m = k - n * mt;
@@ -90,9 +121,8 @@ __global__ __launch_bounds__(256) void moe_place_kernel(const MoeRouteArgs a)
 
 hipError_t launch_moe_route(const MoeRouteArgs& a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(moe_count_kernel, dim3(a.E), dim3(256), 0, stream, a);
-    hipLaunchKernelGGL(moe_prefix_kernel, dim3(1), dim3(256), 0, stream, a);
-    hipLaunchKernelGGL(moe_place_kernel, dim3(a.E), dim3(256), 0, stream, a);
+    if (a.E > kMaxExperts) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(moe_route_kernel, dim3(a.E), dim3(256), (size_t)a.E * sizeof(int), stream, a);
     return hipGetLastError();
 }
 
