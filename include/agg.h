@@ -43,6 +43,7 @@ enum { AGG_B_NK = 0,                         /* B stored [N][K], K contiguous (w
        AGG_B_KN = 1 };                       /* B stored [K][N], N contiguous */
 enum { AGG_PRODUCER_KERNEL = 0,              /* copy kernel on a few CUs, release-stores the signals */
        AGG_PRODUCER_SDMA = 1,               /* copy engine (no compute units) + one 4-byte copy per signal */
+       AGG_PRODUCER_LINKS = 2,              /* full mesh: every peer's shard on a "link" of its own, all at once, chunk by chunk */
        AGG_PRODUCER_SKIP_LOCAL = 0x100 };    /* OR into mode: do not (re)copy the local shard in this call */
 
 /* One signal word per AGG_SIGNAL_STRIDE int32 (each signal owns a 128-byte line). */
@@ -109,7 +110,10 @@ int agg_status(agg_ctx* ctx);
  * order rank+1, rank+2, ... and n_arrivals is ignored), L_r is copied to T + r*shard_bytes chunk by chunk
  * and each chunk's signal is set (release) once the chunk has landed.  Shards not listed never arrive.
  * mode: AGG_PRODUCER_KERNEL uses `n_workgroups` workgroups (0 = one per compute unit) whose registers fit beside
- * the consumer's on every CU; AGG_PRODUCER_SDMA uses hipMemcpyAsync without compute units.
+ * the consumer's on every CU; AGG_PRODUCER_SDMA uses hipMemcpyAsync without compute units; AGG_PRODUCER_LINKS
+ * (Section 3.7, full mesh) copies the local shard first and then all listed peers side by side, each on an equal
+ * share of the workgroups, chunk after chunk, optionally held to agg_set_link_rate: chunk c of every peer then
+ * arrives at about (c + 1) * chunk_bytes / rate, whatever the order of the list.
  */
 int ag_producer_emulate(agg_ctx* ctx, const void* const* remote_shards, const int* arrival_order,
                         int n_arrivals, int mode, int n_workgroups, void* producer_stream);
@@ -178,6 +182,20 @@ int ag_moe_gemm(agg_ctx* ctx, int Ttok, int topk, int E, int N, int K,
                 const int32_t* topk_ids, const void* weights,
                 int32_t* sorted_token, int32_t* sorted_expert_offsets,
                 void* Y, int ldy, int y_dtype, void* stream);
+
+/*
+ * Order in which ag_gemm walks the m-tiles (Section 3.7).  AGG_ORDER_ROTATED (default): the local shard, then the
+ * peers' shards whole, in pull order rank+1, rank+2, ... -- matches a producer that delivers one shard after the
+ * other (a switched fabric).  AGG_ORDER_SUBCHUNK: the local shard, then the first chunk of every peer, the second
+ * chunk of every peer, ... -- matches AGG_PRODUCER_LINKS (a full mesh, every peer on its own link).  It needs
+ * shards and chunks that are whole numbers of tile rows and is otherwise ignored.  The result is the same bit for
+ * bit in either order.
+ */
+enum { AGG_ORDER_ROTATED = 0, AGG_ORDER_SUBCHUNK = 1 };
+int agg_set_tile_order(agg_ctx* ctx, int order);
+
+/* Pace of one link of AGG_PRODUCER_LINKS in GB/s (1e9 bytes per second); 0 (default) = as fast as the copy goes. */
+int agg_set_link_rate(agg_ctx* ctx, double gigabytes_per_second);
 
 /* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 128x128.  A tuning knob (Section 3.8); every shape gives the same result up to fp32 summation order. */
 int agg_set_tile_config(agg_ctx* ctx, int tile_config);

@@ -27,6 +27,8 @@ struct GemmParams {
     int panel_m;          // m-tiles per panel (a panel = the tiles of one shard step)
     int group_n;          // n-tiles per L2 block inside a panel
     int m_tile_start;     // m-tile holding this rank's first row
+    int order;            // AGG_ORDER_*: how the m-tiles are walked
+    int tiles_per_shard, tiles_per_chunk, world, rank;   // for the sub-chunk order
     // signals (nullptr = un-gated)
     const int* flags;
     int epoch;
@@ -92,8 +94,11 @@ struct ProducerArgs {
     int* counters;
     int epoch;
     int team;                     // workgroups that share one chunk (set by launch_producer)
+    int link_wgs;                 // full-mesh mode: workgroups per link (set by launch_producer_links)
+    double ticks_per_byte;        // full-mesh mode: wall-clock ticks a link takes per byte (0 = not paced)
 };
 hipError_t launch_producer(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
+hipError_t launch_producer_links(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_signal_set(int* flag, int value, hipStream_t stream);
 
 struct ReduceArgs {
@@ -130,6 +135,8 @@ struct agg_ctx {
     int* epoch_word;     // device copy of the epoch (source of the SDMA signal copies)
     int device;
     int tile_config;     // -1 = automatic
+    int tile_order;      // AGG_ORDER_*
+    double link_GBps;    // pace of a link of the full-mesh producer (0 = not paced)
     hipStream_t producer_stream, consumer_stream;
     // grouped GEMM workspace (grown on demand by ag_moe_gemm)
     int* moe_ws;          // counts[E] | tile_first[E+1] | n_tiles

@@ -184,6 +184,20 @@ int agg_set_wait_limit_us(agg_ctx* c, uint64_t us)
     return AGG_OK;
 }
 
+int agg_set_tile_order(agg_ctx* c, int order)
+{
+    if (!c || (order != AGG_ORDER_ROTATED && order != AGG_ORDER_SUBCHUNK)) return AGG_ERR_INVALID_ARG;
+    c->tile_order = order;
+    return AGG_OK;
+}
+
+int agg_set_link_rate(agg_ctx* c, double gigabytes_per_second)
+{
+    if (!c || !(gigabytes_per_second >= 0.0) || gigabytes_per_second > 1e6) return AGG_ERR_INVALID_ARG;
+    c->link_GBps = gigabytes_per_second;
+    return AGG_OK;
+}
+
 int agg_set_tile_config(agg_ctx* c, int cfg)
 {
     if (!c || cfg < -1 || cfg >= TILE_CONFIGS) return AGG_ERR_INVALID_ARG;
@@ -211,7 +225,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     if (!c || !remote_shards) return AGG_ERR_INVALID_ARG;
     const bool skip_local = (mode & AGG_PRODUCER_SKIP_LOCAL) != 0;
     mode &= ~AGG_PRODUCER_SKIP_LOCAL;
-    if (mode != AGG_PRODUCER_KERNEL && mode != AGG_PRODUCER_SDMA) return AGG_ERR_INVALID_ARG;
+    if (mode != AGG_PRODUCER_KERNEL && mode != AGG_PRODUCER_SDMA && mode != AGG_PRODUCER_LINKS) return AGG_ERR_INVALID_ARG;
     if (n_workgroups < 0 || n_workgroups > 4096) return AGG_ERR_INVALID_ARG;
     const int W = c->W;
     if (arrival_order && (n_arrivals < 0 || n_arrivals > W - 1)) return AGG_ERR_INVALID_ARG;
@@ -246,6 +260,27 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     if (mode == AGG_PRODUCER_KERNEL) {
         const int nwg = n_workgroups > 0 ? n_workgroups : c->num_cus;
         return hip_fail(launch_producer(a, nwg, st));
+    }
+    if (mode == AGG_PRODUCER_LINKS) {
+        // the local copy first, at full width (it crosses no link); then every peer on a link of its own
+        const int nwg = n_workgroups > 0 ? n_workgroups : c->num_cus;
+        int first_remote = 0;
+        if (!skip_local) {
+            ProducerArgs loc = a;
+            loc.n_jobs = 1;
+            int rc = hip_fail(launch_producer(loc, nwg, st));
+            if (rc != AGG_OK) return rc;
+            first_remote = 1;
+        }
+        ProducerArgs rem = a;
+        rem.n_jobs = a.n_jobs - first_remote;
+        for (int j = 0; j < rem.n_jobs; ++j) {
+            rem.src[j] = a.src[j + first_remote];
+            rem.rank_of[j] = a.rank_of[j + first_remote];
+        }
+        // wall-clock ticks per byte of one link
+        rem.ticks_per_byte = c->link_GBps > 0.0 ? ((double)c->wall_khz * 1e3) / (c->link_GBps * 1e9) : 0.0;
+        return hip_fail(launch_producer_links(rem, nwg, st));
     }
     // copy engine: one transfer per chunk, then "another data transfer solely for signals" (Section 3.6)
     HIP_TRY(launch_signal_set(c->epoch_word, c->epoch, st));
@@ -288,6 +323,18 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     p.c_vec_ok = aligned16(C) && ((long long)ldc * (p.c_is_f32 ? 4 : 2)) % 16 == 0;
     const int cfg = choose_tile(c, M, N);
     fill_schedule(p, cfg, Ms, c->rank * Ms);
+    {
+        // sub-chunk order (Section 3.7, full mesh): possible when shards and chunks are whole numbers of tiles
+        const TileShape t = tile_shape(cfg);
+        const int rows_per_chunk = Ms / cps;
+        if (c->tile_order == AGG_ORDER_SUBCHUNK && Ms % t.bm == 0 && rows_per_chunk % t.bm == 0) {
+            p.order = AGG_ORDER_SUBCHUNK;
+            p.tiles_per_shard = Ms / t.bm;
+            p.tiles_per_chunk = rows_per_chunk / t.bm;
+            p.world = c->W;
+            p.rank = c->rank;
+        }
+    }
     p.flags = c->signals;
     p.epoch = c->epoch;
     p.rows_per_flag = Ms / cps;

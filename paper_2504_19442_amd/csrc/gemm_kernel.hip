@@ -201,7 +201,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             const int gn = min(p.group_n, p.tiles_n - blk * p.group_n);
             const int mi = r / gn;
             n_tile = blk * p.group_n + (r - mi * gn);
-            m_tile = (p.m_tile_start + panel * p.panel_m + mi) % p.tiles_m;
+            const int v = panel * p.panel_m + mi;            // place in the order of m-tiles
+            if (p.order == AGG_ORDER_SUBCHUNK) {
+                // the local shard, then sub-chunk 0 of every peer (in pull order), sub-chunk 1 of every peer, ...
+                if (v < p.tiles_per_shard) {
+                    m_tile = p.rank * p.tiles_per_shard + v;
+                } else {
+                    const int v2 = v - p.tiles_per_shard;
+                    const int per_c = (p.world - 1) * p.tiles_per_chunk;
+                    const int c = v2 / per_c, rem = v2 - c * per_c;
+                    const int jj = rem / p.tiles_per_chunk, k = rem - jj * p.tiles_per_chunk;
+                    const int shard = (p.rank + 1 + jj) % p.world;
+                    m_tile = shard * p.tiles_per_shard + c * p.tiles_per_chunk + k;
+                }
+            } else {
+                m_tile = (p.m_tile_start + v) % p.tiles_m;
+            }
             m0 = m_tile * BM;
             n0 = n_tile * BN;
             m_lim = p.M;

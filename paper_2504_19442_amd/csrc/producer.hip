@@ -13,7 +13,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 // inside a team each workgroup copies one contiguous slice of the chunk; several chunks are in flight at
 // once, which is also how a full mesh of links delivers (Section 3.7).
 //
-// The stores are write-through at system scope (sc0 sc1): the data goes to memory instead of staying
+// The stores are write-through at agent scope (sc1): the data goes to memory instead of staying
 // dirty in the L2 of the XCD the workgroup happens to run on, so no L2 write-back is needed before the
 // signal -- a wait for the stores to complete is the release.  (An agent-scope release fence would write
 // back the whole L2, once per workgroup and chunk, and that cost more than the copy itself.)  The consumer's
@@ -69,6 +69,64 @@ __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
     }
 }
 
+// Full-mesh arrival (Section 3.7, the AMD case: a rank pulls from all its peers at once, one link each, and a
+// shard arrives sub-chunk by sub-chunk).  Every job is one link served by link_wgs workgroups of its own; a link
+// moves its shard chunk after chunk and sets each chunk's signal.  With ticks_per_byte > 0 a link is held to that
+// rate: before each 16 KiB step a workgroup waits until the link's clock allows the bytes moved so far, so chunk c
+// of every peer lands at about (c + 1) * chunk_bytes / rate after the start -- the arrival pattern of real links.
+// The wait ends at a time computed beforehand, so it is bounded.
+__global__ __launch_bounds__(256) void producer_links_kernel(const ProducerArgs a)
+{
+    const int tid = threadIdx.x;
+    const int link = blockIdx.x % a.n_jobs, j = blockIdx.x / a.n_jobs;
+    if (j >= a.link_wgs) return;
+    const long long t0 = wall_clock64();
+    const long long vec_per_chunk = a.chunk_bytes / 16;
+    const long long per_wg = (vec_per_chunk + a.link_wgs - 1) / a.link_wgs;
+    const long long lo = j * per_wg, hi = lo + per_wg < vec_per_chunk ? lo + per_wg : vec_per_chunk;
+    const unsigned bytes = hi > lo ? (unsigned)((hi - lo) * 16) : 0u;
+    const int r = a.rank_of[link];
+    constexpr int NT = 2, WT = 16;
+    for (int c = 0; c < a.chunks_per_shard; ++c) {
+        const char* s = (const char*)a.src[link] + (c * vec_per_chunk + lo) * 16;
+        char* d = a.T + (long long)r * a.shard_bytes + (c * vec_per_chunk + lo) * 16;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(s), 0, bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(d, 0, bytes, 0x00020000);
+        int step = 0;
+        for (unsigned off = tid * 16u; off - tid * 16u < bytes; off += 4u * 4096u, ++step) {
+            if (a.ticks_per_byte > 0.0) {
+                // bytes the link has moved when all its workgroups have done `step` steps of this chunk
+                const double before = (double)c * (double)a.chunk_bytes + (double)step * 16384.0 * a.link_wgs;
+                const long long target = t0 + (long long)(before * a.ticks_per_byte);
+                while (wall_clock64() < target) __builtin_amdgcn_s_sleep(4);
+            }
+            u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, NT);
+            u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 4096u, 0, NT);
+            u32x4 v2 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 8192u, 0, NT);
+            u32x4 v3 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 12288u, 0, NT);
+            __builtin_amdgcn_raw_buffer_store_b128(v0, rd, off, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v1, rd, off + 4096u, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v2, rd, off + 8192u, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v3, rd, off + 12288u, 0, WT);
+        }
+        if (a.ticks_per_byte > 0.0) {      // the chunk is not announced before the link could have delivered it
+            const long long target = t0 + (long long)((double)(c + 1) * (double)a.chunk_bytes * a.ticks_per_byte);
+            while (wall_clock64() < target) __builtin_amdgcn_s_sleep(4);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (tid == 0) {
+            const int f = r * a.chunks_per_shard + c;
+            const int prev = __hip_atomic_fetch_add(a.counters + f, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (prev == a.link_wgs - 1) {
+                __hip_atomic_store(a.counters + f, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.flags + (long long)f * kSignalStride, a.epoch, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
 __global__ void signal_set_kernel(int* flag, int value)
 {
     __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
@@ -83,6 +141,21 @@ hipError_t launch_producer(const ProducerArgs& a_in, int n_workgroups, hipStream
     if (team > n_workgroups) team = n_workgroups;
     a.team = (int)team;
     hipLaunchKernelGGL(producer_kernel, dim3(n_workgroups), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+// All jobs of `a` are links that run side by side; the grid is shared out evenly among them.
+hipError_t launch_producer_links(const ProducerArgs& a_in, int n_workgroups, hipStream_t stream)
+{
+    ProducerArgs a = a_in;
+    if (a.n_jobs < 1) return hipSuccess;
+    int per_link = n_workgroups / a.n_jobs;
+    if (per_link < 1) per_link = 1;
+    // no more workgroups on a link than it has 16 KiB steps in a chunk
+    const long long steps = (a.chunk_bytes + 16383) / 16384;
+    if (per_link > steps) per_link = (int)steps;
+    a.link_wgs = per_link;
+    hipLaunchKernelGGL(producer_links_kernel, dim3(per_link * a.n_jobs), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -227,3 +227,95 @@ def test_full_size_sampled_rows_and_order_invariance(shape, n_orders):
                 assert np.array_equal(C16, base16), f"arrival order {order} changed the output bits"
     finally:
         run.close()
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# Full-mesh arrival (every peer on a link of its own, chunk by chunk) and the sub-chunk tile order (Section 3.7)
+# ----------------------------------------------------------------------------------------------------------------
+
+MESH_SHAPE = wl.AgGemmShape("ag_mesh_small", 10, 4, 256, 128, 256)
+
+
+@pytest.mark.parametrize("rank", [0, 3])
+def test_full_mesh_producer_and_subchunk_order_match_the_plain_run_bit_for_bit(rank):
+    inp = wl.make_ag_gemm(MESH_SHAPE)
+    want = oracle.ag_gemm(inp.shards, inp.B_kn, rank)
+    run = AgGemmRun(inp, rank, chunks_per_shard=2)
+    try:
+        base = run.run(tile=1).cpu().numpy()                       # rotated order, shard-after-shard producer
+        got64 = base.astype(np.float64)
+        assert np.linalg.norm(got64 - want) / np.linalg.norm(want) <= 1e-4
+        assert np.abs(got64 - want).max() <= 1e-3 * np.sqrt(MESH_SHAPE.K)
+        for order in (agg.ORDER_SUBCHUNK, agg.ORDER_ROTATED):
+            for rate in (0.0, 2.0):                                 # unpaced; 2 GB/s: a 64 KiB shard takes 32 us
+                for tile in (1, 0):                                 # 128-row tiles walk sub-chunks; 256-row tiles cannot
+                    run.ctx.set_tile_order(order)
+                    run.ctx.set_link_rate(rate)
+                    C = run.run(tile=tile, mode=agg.PRODUCER_LINKS, consumer_first=(tile == 1)).cpu().numpy()
+                    if tile == 1:
+                        assert np.array_equal(C.view(np.uint32), base.view(np.uint32)), (order, rate)
+                    else:
+                        assert np.abs(C.astype(np.float64) - want).max() <= 1e-3 * np.sqrt(MESH_SHAPE.K)
+        # a subset of the peers, listed in any order: the others never arrive and the consumer reports it
+        run.ctx.set_wait_limit_us(20000)
+        run.ctx.set_tile_order(agg.ORDER_SUBCHUNK)
+        run.poison()
+        agg.signal_reset(run.ctx)
+        C = torch.zeros((MESH_SHAPE.M, MESH_SHAPE.N), device="cuda", dtype=torch.float32)
+        peers = [(rank + j) % MESH_SHAPE.W for j in (3, 1)]
+        agg.ag_producer_emulate(run.ctx, run.remote, peers, agg.PRODUCER_LINKS, 0, run.prod)
+        agg.ag_gemm(run.ctx, MESH_SHAPE.M, MESH_SHAPE.N, MESH_SHAPE.K, run.B_nk, MESH_SHAPE.K, agg.B_NK, C,
+                    MESH_SHAPE.N, agg.F32, run.cons)
+        torch.cuda.synchronize()
+        assert agg.agg_status(run.ctx) == agg.ERR_TIMEOUT
+    finally:
+        run.close()
+
+
+def test_paced_links_deliver_at_the_link_rate():
+    sh = wl.AG_8B                                                   # 4 MiB shards
+    inp = wl.make_ag_gemm(sh)
+    run = AgGemmRun(inp, 2, chunks_per_shard=4)
+    try:
+        rate = 40.0                                                 # GB/s per link: 4 MiB take 104.9 us
+        run.ctx.set_link_rate(rate)
+        expect_ms = sh.Ms * sh.K * 2 / (rate * 1e9) * 1e3
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        times = []
+        for _ in range(3):
+            agg.signal_reset(run.ctx)
+            e0.record(run.prod)
+            agg.ag_producer_emulate(run.ctx, run.remote, None, agg.PRODUCER_LINKS, 0, run.prod)
+            e1.record(run.prod)
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        assert agg.agg_status(run.ctx) == agg.OK
+        t = min(times)
+        assert 0.95 * expect_ms <= t <= 3.0 * expect_ms, (t, expect_ms)      # never faster than the link
+        # and the data is all there
+        T = run.ctx.staging
+        from gpu_util import _tensor_from_ptr
+        got = host_bits(_tensor_from_ptr(T, sh.W * sh.Ms * sh.K)).reshape(sh.M, sh.K)
+        assert np.array_equal(got, np.concatenate(inp.shards))
+    finally:
+        run.close()
+
+
+def test_full_size_full_mesh_paced_subchunk_order():
+    sh = wl.AG_70B
+    inp = wl.make_ag_gemm(sh)
+    rank = 5
+    run = AgGemmRun(inp, rank, chunks_per_shard=4)
+    try:
+        base = run.run(out_dtype=agg.BF16, consumer_first=False)
+        run.ctx.set_tile_order(agg.ORDER_SUBCHUNK)
+        run.ctx.set_link_rate(76.8)
+        C = run.run(out_dtype=agg.BF16, mode=agg.PRODUCER_LINKS, consumer_first=True)
+        assert torch.equal(C.view(torch.int16), base.view(torch.int16))
+        rows = np.sort(np.random.default_rng(3).choice(sh.M, size=8, replace=False))
+        want = oracle.ag_gemm(inp.shards, inp.B_kn, rank, rows=rows)
+        got = bits_to_f64(host_bits(C[torch.from_numpy(rows).cuda()]))
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7)
+        assert np.all(np.abs(got - want) <= 0.5 * ulp + 1e-3 * np.sqrt(sh.K) * 2.0 ** -8)
+    finally:
+        run.close()
