@@ -86,6 +86,8 @@ def main() -> int:
     ap.add_argument("--tile", type=int, default=-1)
     ap.add_argument("--chunks", type=int, default=4, help="signals per shard")
     ap.add_argument("--producer-wgs", type=int, default=0)
+    ap.add_argument("--link-gbps", type=float, default=76.8,
+                    help="rate of one emulated link of the full-mesh block (one direction of an xGMI link)")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="profiling aid: also run one plain 256 MiB device copy, the known-size kernel that the "
@@ -240,6 +242,49 @@ def main() -> int:
             "fused_over_gemm": round(t_fused2 / t_gemm, 4),
             "protocol": f"medians of {rounds} alternating rounds of {n2} steps",
         }
+        # Full-mesh arrival at link rate (Section 3.7, the AMD case): all 7 peers at once, each on a link held to
+        # `--link-gbps`, chunk by chunk; consumer in sub-chunk order, and in shard order for contrast
+        ctx.set_link_rate(args.link_gbps)
+
+        def step_mesh():
+            agg.signal_reset(ctx)
+            hev.wait(prod_h, ev_cons_done)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS, args.producer_wgs, prod)
+            agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
+            hev.record(ev_cons_done, cons_h)
+
+        def step_mesh_copy():
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS, args.producer_wgs, prod)
+
+        def step_mesh_serial():
+            agg.signal_reset(ctx)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS, args.producer_wgs, cons)
+            agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
+
+        mesh = {"sub": [], "rot": [], "copy": [], "serial": []}
+        n3 = max(5, args.steps // 10)
+        for _ in range(3):
+            hev.record(ev_cons_done, cons_h)
+            ctx.set_tile_order(agg.ORDER_SUBCHUNK)
+            mesh["sub"].append(timed(step_mesh, n3, 2))
+            ctx.set_tile_order(agg.ORDER_ROTATED)
+            mesh["rot"].append(timed(step_mesh, n3, 2))
+            mesh["copy"].append(timed(step_mesh_copy, n3, 2))
+            mesh["serial"].append(timed(step_mesh_serial, n3, 2))
+        assert agg.agg_status(ctx) == agg.OK
+        ctx.set_link_rate(0.0)
+        m_sub, m_rot, m_copy, m_serial = (float(np.median(mesh[k])) for k in ("sub", "rot", "copy", "serial"))
+        out["full_mesh"] = {
+            "link_GBps": args.link_gbps, "links": shape.W - 1,
+            "t_copy_ms": round(m_copy * 1e3, 4), "t_serial_ms": round(m_serial * 1e3, 4),
+            "t_fused_subchunk_order_ms": round(m_sub * 1e3, 4), "t_fused_shard_order_ms": round(m_rot * 1e3, 4),
+            "tflops_subchunk_order": round(flops / m_sub / 1e12, 2),
+            "overlap_efficiency": round(m_serial / m_sub, 4),
+            "hidden_fraction": round((m_serial - m_sub) / m_copy, 4),
+            "hidden_fraction_shard_order": round((m_serial - m_rot) / m_copy, 4),
+            "protocol": f"medians of 3 alternating rounds of {n3} steps",
+        }
+
         # the reducer of GEMM+ReduceScatter at its full size (all signals set: pure streaming reduction)
         rs = wl.RS_FULL
         slots = [torch.randn((rs.Ms, rs.N), device="cuda", dtype=torch.float32) for _ in range(rs.W)]
