@@ -85,6 +85,9 @@ __device__ __forceinline__ float acc_read()
     return x;
 }
 
+#ifndef AGG_LOAD_AUX
+#define AGG_LOAD_AUX 0                 // cache policy bits of the global->LDS loads
+#endif
 constexpr int BK = 64;                 // bf16 per stage
 constexpr int ROW_BYTES = BK * 2;      // 128-byte rows in LDS: one cache line per row and stage
 constexpr int UNIT_ROWS = 8;           // one wave-wide 16-byte-per-lane load covers 8 rows
@@ -290,7 +293,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             constexpr bool is_a = 4 * i < C_::A_UNITS;      // the same for all four waves
             unsigned char* dst = lds + pos * 4096 + wave * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
-                                                     ks * ROW_BYTES, 0, 0);
+                                                     ks * ROW_BYTES, 0, AGG_LOAD_AUX);
         };
 
         // two fragment sets, one per parity of the quarter-step.  Fragment f < MB is the A fragment of row

@@ -319,3 +319,16 @@ def test_full_size_full_mesh_paced_subchunk_order():
         assert np.all(np.abs(got - want) <= 0.5 * ulp + 1e-3 * np.sqrt(sh.K) * 2.0 ** -8)
     finally:
         run.close()
+
+
+def test_world_of_one_is_a_plain_gemm():
+    sh = wl.AgGemmShape("ag_w1", 12, 1, 200, 192, 136)
+    inp = wl.make_ag_gemm(sh)
+    want = oracle.gemm(inp.shards[0], inp.B_kn)
+    assert np.array_equal(want, oracle.ag_gemm(inp.shards, inp.B_kn, 0))
+    run = AgGemmRun(inp, 0)
+    try:
+        for tile in (0, 1):
+            check_f32(run.run(tile=tile).cpu().numpy(), want, sh.K)
+    finally:
+        run.close()
