@@ -86,6 +86,9 @@ def main() -> int:
     ap.add_argument("--tile", type=int, default=-1)
     ap.add_argument("--chunks", type=int, default=4, help="signals per shard")
     ap.add_argument("--producer-wgs", type=int, default=0)
+    ap.add_argument("--t-local", action="store_true",
+                    help="read the own shard from T like any other (default: in place, where the caller keeps it, "
+                         "with the local copy into T done last)")
     ap.add_argument("--link-gbps", type=float, default=76.8,
                     help="rate of one emulated link of the full-mesh block (one direction of an xGMI link)")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the CPU oracle is timed on (0 = skip)")
@@ -119,6 +122,10 @@ def main() -> int:
     run = AgGemmRun(inp, rank, chunks_per_shard=args.chunks)
     ctx = run.ctx
     ctx.set_tile_config(args.tile)
+    local_flag = 0
+    if not args.t_local:
+        ctx.set_local_shard(run.remote[rank])
+        local_flag = agg.PRODUCER_LOCAL_LAST
     M, N, K = shape.M, shape.N, shape.K
     C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
     prod, cons = run.prod, run.cons
@@ -129,7 +136,7 @@ def main() -> int:
     def step_fused(ev_pairs=None):
         agg.signal_reset(ctx)
         hev.wait(prod_h, ev_cons_done)         # T is shared: the next arrival waits for the last consumer
-        agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, prod)
+        agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL | local_flag, args.producer_wgs, prod)
         if ev_pairs is not None:
             e0, e1 = ev_pairs[step_fused.k]
             step_fused.k += 1
@@ -153,7 +160,7 @@ def main() -> int:
 
     if args.only_gemm:
         agg.signal_reset(ctx)
-        agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, prod)
+        agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL | local_flag, args.producer_wgs, prod)
         torch.cuda.synchronize()
         t = timed(lambda: agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons), args.steps,
                   args.warmup)
@@ -194,7 +201,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": shape.name, "W": shape.W, "rank": rank, "M": M, "N": N, "K": K,
                    "signals_per_shard": args.chunks, "tile_config": args.tile, "out": "bf16",
-                   "producer": "copy kernel on the producer stream"},
+                   "producer": "copy kernel on the producer stream",
+                   "own_shard": "from T" if args.t_local else "read in place, copied into T last"},
         "fraction_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": {"bound": "mfma", "achieved": round(flops / (kern_ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(flops / (kern_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
@@ -208,11 +216,11 @@ def main() -> int:
             agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
 
         def step_copy():
-            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, prod)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL | local_flag, args.producer_wgs, prod)
 
         def step_serial():
             agg.signal_reset(ctx)
-            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL, args.producer_wgs, cons)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL | local_flag, args.producer_wgs, cons)
             agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
 
         # alternate the four measurements over several rounds (clocks drift with load and temperature: taking
@@ -249,16 +257,16 @@ def main() -> int:
         def step_mesh():
             agg.signal_reset(ctx)
             hev.wait(prod_h, ev_cons_done)
-            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS, args.producer_wgs, prod)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS | local_flag, args.producer_wgs, prod)
             agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
             hev.record(ev_cons_done, cons_h)
 
         def step_mesh_copy():
-            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS, args.producer_wgs, prod)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS | local_flag, args.producer_wgs, prod)
 
         def step_mesh_serial():
             agg.signal_reset(ctx)
-            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS, args.producer_wgs, cons)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_LINKS | local_flag, args.producer_wgs, cons)
             agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
 
         mesh = {"sub": [], "rot": [], "copy": [], "serial": []}

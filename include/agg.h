@@ -44,7 +44,8 @@ enum { AGG_B_NK = 0,                         /* B stored [N][K], K contiguous (w
 enum { AGG_PRODUCER_KERNEL = 0,              /* copy kernel on a few CUs, release-stores the signals */
        AGG_PRODUCER_SDMA = 1,               /* copy engine (no compute units) + one 4-byte copy per signal */
        AGG_PRODUCER_LINKS = 2,              /* full mesh: every peer's shard on a "link" of its own, all at once, chunk by chunk */
-       AGG_PRODUCER_SKIP_LOCAL = 0x100 };    /* OR into mode: do not (re)copy the local shard in this call */
+       AGG_PRODUCER_SKIP_LOCAL = 0x100,     /* OR into mode: do not (re)copy the local shard in this call */
+       AGG_PRODUCER_LOCAL_LAST = 0x200 };    /* OR into mode: copy the local shard after the peers' instead of first */
 
 /* One signal word per AGG_SIGNAL_STRIDE int32 (each signal owns a 128-byte line). */
 #define AGG_SIGNAL_STRIDE 32
@@ -182,6 +183,15 @@ int ag_moe_gemm(agg_ctx* ctx, int Ttok, int topk, int E, int N, int K,
                 const int32_t* topk_ids, const void* weights,
                 int32_t* sorted_token, int32_t* sorted_expert_offsets,
                 void* Y, int ldy, int y_dtype, void* stream);
+
+/*
+ * Let ag_gemm read this rank's own shard from `local_shard` (DEVICE pointer to L_rank, [Ms][K] bf16, 16-byte aligned,
+ * borrowed until reset with NULL) instead of from T: tiles that lie wholly inside the own shard then wait for nothing
+ * and start before any copy has landed.  T is still completed by the producer; with AGG_PRODUCER_LOCAL_LAST the local
+ * copy, which nobody waits for any more, is done after the peers'.  The caller must not modify L_rank while ag_gemm
+ * runs.  Same result bit for bit.
+ */
+int agg_set_local_shard(agg_ctx* ctx, const void* local_shard);
 
 /*
  * Order in which ag_gemm walks the m-tiles (Section 3.7).  AGG_ORDER_ROTATED (default): the local shard, then the

@@ -13,7 +13,7 @@ import os
 __all__ = [
     "AggError", "Ctx", "symm_alloc", "signal_reset", "signal_set", "ag_producer_emulate", "ag_gemm",
     "rs_reduce", "gemm_rs", "ag_moe_gemm", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
-    "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL",
+    "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL", "PRODUCER_LOCAL_LAST",
     "ORDER_ROTATED", "ORDER_SUBCHUNK", "SIGNAL_STRIDE",
     "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM",
     "EXPORTS",
@@ -21,7 +21,7 @@ __all__ = [
 
 BF16, F32 = 0, 1
 B_NK, B_KN = 0, 1
-PRODUCER_KERNEL, PRODUCER_SDMA, PRODUCER_LINKS, PRODUCER_SKIP_LOCAL = 0, 1, 2, 0x100
+PRODUCER_KERNEL, PRODUCER_SDMA, PRODUCER_LINKS, PRODUCER_SKIP_LOCAL, PRODUCER_LOCAL_LAST = 0, 1, 2, 0x100, 0x200
 ORDER_ROTATED, ORDER_SUBCHUNK = 0, 1
 SIGNAL_STRIDE = 32
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT, ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
@@ -30,7 +30,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT
 EXPORTS = [
     "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
     "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs",
-    "ag_moe_gemm", "agg_set_tile_config", "agg_set_tile_order", "agg_set_link_rate", "agg_strerror", "agg_device_info",
+    "ag_moe_gemm", "agg_set_tile_config", "agg_set_tile_order", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
 ]
 
 
@@ -65,6 +65,7 @@ def _lib() -> C.CDLL:
         L.agg_set_wait_limit_us.argtypes = [vp, u64]
         L.agg_set_tile_config.argtypes = [vp, i32]
         L.agg_set_tile_order.argtypes = [vp, i32]
+        L.agg_set_local_shard.argtypes = [vp, vp]
         L.agg_set_link_rate.argtypes = [vp, C.c_double]
         L.agg_status.argtypes = [vp]
         L.ag_producer_emulate.argtypes = [vp, C.POINTER(vp), C.POINTER(i32), i32, i32, i32, vp]
@@ -151,6 +152,9 @@ class Ctx:
 
     def set_tile_order(self, order: int) -> None:
         _check(_lib().agg_set_tile_order(self.handle, int(order)), "agg_set_tile_order")
+
+    def set_local_shard(self, local_shard) -> None:
+        _check(_lib().agg_set_local_shard(self.handle, _ptr(local_shard)), "agg_set_local_shard")
 
     def set_link_rate(self, gigabytes_per_second: float) -> None:
         _check(_lib().agg_set_link_rate(self.handle, float(gigabytes_per_second)), "agg_set_link_rate")

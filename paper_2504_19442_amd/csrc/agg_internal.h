@@ -15,6 +15,8 @@ constexpr int kSignalStride = AGG_SIGNAL_STRIDE;
 // B is [N][K] bf16 (K contiguous), C row-major.
 struct GemmParams {
     const uint16_t* A;
+    const uint16_t* A_local;   // AllGather-GEMM: this rank's own shard where the caller keeps it (nullptr = read it from A)
+    int local_lo, local_hi;    // its rows in A
     const uint16_t* B;
     void* C;              // rows outside [own_lo, own_hi) (or every row if C_own == nullptr)
     void* C_own;          // GEMM-RS: rows [own_lo, own_hi) go here, at row index (row - own_lo)
@@ -136,6 +138,7 @@ struct agg_ctx {
     int device;
     int tile_config;     // -1 = automatic
     int tile_order;      // AGG_ORDER_*
+    const void* local_shard;  // see agg_set_local_shard
     double link_GBps;    // pace of a link of the full-mesh producer (0 = not paced)
     hipStream_t producer_stream, consumer_stream;
     // grouped GEMM workspace (grown on demand by ag_moe_gemm)

@@ -184,6 +184,14 @@ int agg_set_wait_limit_us(agg_ctx* c, uint64_t us)
     return AGG_OK;
 }
 
+int agg_set_local_shard(agg_ctx* c, const void* local_shard)
+{
+    if (!c) return AGG_ERR_INVALID_ARG;
+    if (local_shard && !aligned16(local_shard)) return AGG_ERR_MISALIGNED;
+    c->local_shard = local_shard;
+    return AGG_OK;
+}
+
 int agg_set_tile_order(agg_ctx* c, int order)
 {
     if (!c || (order != AGG_ORDER_ROTATED && order != AGG_ORDER_SUBCHUNK)) return AGG_ERR_INVALID_ARG;
@@ -224,7 +232,8 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
 {
     if (!c || !remote_shards) return AGG_ERR_INVALID_ARG;
     const bool skip_local = (mode & AGG_PRODUCER_SKIP_LOCAL) != 0;
-    mode &= ~AGG_PRODUCER_SKIP_LOCAL;
+    const bool local_last = (mode & AGG_PRODUCER_LOCAL_LAST) != 0 && !skip_local;
+    mode &= ~(AGG_PRODUCER_SKIP_LOCAL | AGG_PRODUCER_LOCAL_LAST);
     if (mode != AGG_PRODUCER_KERNEL && mode != AGG_PRODUCER_SDMA && mode != AGG_PRODUCER_LINKS) return AGG_ERR_INVALID_ARG;
     if (n_workgroups < 0 || n_workgroups > 4096) return AGG_ERR_INVALID_ARG;
     const int W = c->W;
@@ -234,7 +243,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     ProducerArgs a{};
     bool used[kMaxWorld] = {false};
     a.n_jobs = 0;
-    if (!skip_local) a.rank_of[a.n_jobs++] = c->rank;   // the local copy comes first (Algorithm 2)
+    if (!skip_local && !local_last) a.rank_of[a.n_jobs++] = c->rank;   // the local copy comes first (Algorithm 2)
     used[c->rank] = true;
     const int n = arrival_order ? n_arrivals : W - 1;
     for (int j = 0; j < n; ++j) {
@@ -243,6 +252,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
         used[r] = true;
         a.rank_of[a.n_jobs++] = r;
     }
+    if (local_last) a.rank_of[a.n_jobs++] = c->rank;   // ... or last, for a consumer that reads its own shard in place
     for (int j = 0; j < a.n_jobs; ++j) {
         a.src[j] = remote_shards[a.rank_of[j]];
         if (!a.src[j]) return AGG_ERR_INVALID_ARG;
@@ -264,23 +274,30 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     if (mode == AGG_PRODUCER_LINKS) {
         // the local copy first, at full width (it crosses no link); then every peer on a link of its own
         const int nwg = n_workgroups > 0 ? n_workgroups : c->num_cus;
-        int first_remote = 0;
-        if (!skip_local) {
+        const bool has_local = !skip_local;
+        const int first_remote = (has_local && !local_last) ? 1 : 0;
+        const int local_job = local_last ? a.n_jobs - 1 : 0;
+        if (has_local && !local_last) {
             ProducerArgs loc = a;
             loc.n_jobs = 1;
             int rc = hip_fail(launch_producer(loc, nwg, st));
             if (rc != AGG_OK) return rc;
-            first_remote = 1;
         }
         ProducerArgs rem = a;
-        rem.n_jobs = a.n_jobs - first_remote;
+        rem.n_jobs = a.n_jobs - (has_local ? 1 : 0);
         for (int j = 0; j < rem.n_jobs; ++j) {
             rem.src[j] = a.src[j + first_remote];
             rem.rank_of[j] = a.rank_of[j + first_remote];
         }
         // wall-clock ticks per byte of one link
         rem.ticks_per_byte = c->link_GBps > 0.0 ? ((double)c->wall_khz * 1e3) / (c->link_GBps * 1e9) : 0.0;
-        return hip_fail(launch_producer_links(rem, nwg, st));
+        int rc = hip_fail(launch_producer_links(rem, nwg, st));
+        if (rc != AGG_OK || !(has_local && local_last)) return rc;
+        ProducerArgs loc = a;
+        loc.n_jobs = 1;
+        loc.src[0] = a.src[local_job];
+        loc.rank_of[0] = a.rank_of[local_job];
+        return hip_fail(launch_producer(loc, nwg, st));
     }
     // copy engine: one transfer per chunk, then "another data transfer solely for signals" (Section 3.6)
     HIP_TRY(launch_signal_set(c->epoch_word, c->epoch, st));
@@ -311,6 +328,9 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     if (Ms % cps != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
     GemmParams p{};
     p.A = (const uint16_t*)c->staging;
+    p.A_local = (const uint16_t*)c->local_shard;
+    p.local_lo = c->rank * Ms;
+    p.local_hi = p.local_lo + Ms;
     p.B = (const uint16_t*)B;
     p.C = C;
     p.lda = K;

@@ -185,6 +185,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
         if ((G & 7) == 0) t = base + (g & 7) * xcd_slots + (g >> 3); else t = base + g;
         if (t >= total_tiles) continue;
         int m0, n0, m_lim, f_lo = 0, f_hi = -1, expert = 0;
+        bool from_local = false;
         if constexpr (GROUPED) {
             const MoeTile mt = p.tile_tab[t];
             expert = __builtin_amdgcn_readfirstlane(mt.expert);
@@ -223,14 +224,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             m0 = m_tile * BM;
             n0 = n_tile * BN;
             m_lim = p.M;
-            if (p.flags) {
+            // a tile that lies inside this rank's own shard reads it where the caller keeps it: nothing to wait for
+            from_local = p.A_local && m0 >= p.local_lo && m0 + BM <= p.local_hi;
+            if (p.flags && !from_local) {
                 f_lo = m0 / p.rows_per_flag;
                 f_hi = min((min(m0 + BM, p.M) - 1) / p.rows_per_flag, p.n_flags - 1);
             }
         }
 
         // ---- wait for the signals covering rows [m0, min(m0+BM, M))  (wait + consume_token, Section 2.2)
-        if (p.flags) {
+        if (p.flags && f_hi >= f_lo) {
             int gave_up = 0;
             for (int f = f_lo + tid; f <= f_hi; f += 256) {
                 const int* fp = p.flags + (long long)f * kSignalStride;
@@ -263,7 +266,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 #endif
         const __amdgpu_buffer_rsrc_t a_rsrc =
             GROUPED ? make_rsrc(p.A, p.a_bytes)
-                    : make_rsrc(p.A + (long long)m0l * p.lda, (unsigned)(min(BM, p.M - m0l) * (int)p.lda * 2));
+                    : make_rsrc((from_local ? p.A_local + (long long)(m0l - p.local_lo) * p.lda : p.A + (long long)m0l * p.lda),
+                                (unsigned)(min(BM, p.M - m0l) * (int)p.lda * 2));
         const __amdgpu_buffer_rsrc_t b_rsrc =
             make_rsrc(p.B + (GROUPED ? (long long)expert * p.b_group_stride : 0ll) + (long long)n0l * p.ldb,
                       (unsigned)(min(BN, p.N - n0l) * (int)p.ldb * 2));

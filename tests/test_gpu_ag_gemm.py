@@ -332,3 +332,35 @@ def test_world_of_one_is_a_plain_gemm():
             check_f32(run.run(tile=tile).cpu().numpy(), want, sh.K)
     finally:
         run.close()
+
+
+@pytest.mark.parametrize("rank", [0, 2])
+def test_own_shard_read_in_place(rank):
+    """With agg_set_local_shard the consumer never touches the own shard's part of T: it may arrive last, or never."""
+    inp = wl.make_ag_gemm(MESH_SHAPE)
+    run = AgGemmRun(inp, rank, chunks_per_shard=2)
+    sh = MESH_SHAPE
+    try:
+        base = run.run(tile=1).cpu().numpy()
+        run.ctx.set_local_shard(run.remote[rank])
+        for tile in (1, 0):
+            ref = base if tile == 1 else run_plain(run, tile)
+            for mode in (agg.PRODUCER_KERNEL, agg.PRODUCER_LINKS, agg.PRODUCER_SDMA):
+                C = run.run(tile=tile, mode=mode | agg.PRODUCER_LOCAL_LAST).cpu().numpy()
+                assert np.array_equal(C.view(np.uint32), ref.view(np.uint32)), (tile, mode)
+                # T is complete afterwards all the same
+                from gpu_util import _tensor_from_ptr
+                got = host_bits(_tensor_from_ptr(run.ctx.staging, sh.M * sh.K)).reshape(sh.M, sh.K)
+                assert np.array_equal(got, np.concatenate(inp.shards))
+            # the own shard never copied at all: its part of T stays poisoned, the result is still right
+            C = run.run(tile=tile, mode=agg.PRODUCER_KERNEL | agg.PRODUCER_SKIP_LOCAL).cpu().numpy()
+            assert np.array_equal(C.view(np.uint32), ref.view(np.uint32))
+    finally:
+        run.close()
+
+
+def run_plain(run, tile):
+    run.ctx.set_local_shard(None)
+    out = run.run(tile=tile).cpu().numpy()
+    run.ctx.set_local_shard(run.remote[run.rank])
+    return out
