@@ -163,6 +163,25 @@ int gemm_rs(agg_ctx* ctx, int M, int N, int Klocal,
             const float* const* slots, float* P_other,
             void* R, int ldr, int r_dtype, void* gemm_stream, void* reduce_stream);
 
+/*
+ * The GEMM half of GEMM + ReduceScatter with the scatter fused into its epilogue (Section 3.6, "Intra-node
+ * ReduceScatter with Fusion"; Algorithm 3, stream 1): P[M, N] = A_local[M, Klocal] . B_local in fp32, cut into W row
+ * slices of M / W rows.  Slice w is stored straight into slice_dst[w] (HOST array of W DEVICE pointers, each fp32
+ * [M / W, N] row-major, 16-byte aligned -- on a node, rank w's slot for this rank) or, where slice_dst[w] is NULL,
+ * into rows [w*Ms, (w+1)*Ms) of P_other (fp32 [M, N]; may be NULL when no entry of slice_dst is).  When the last tile
+ * of slice w has been stored, *slice_signal[w] (HOST array of W DEVICE pointers to int32 signal words, or NULL, or
+ * NULL entries) is set to this context's epoch with release semantics -- the notify that lets rank w's reducer read
+ * its slot.  Slices are computed starting with first_slice, then first_slice + 1, ... (Section 3.7: a rank starts
+ * with the slices that have to travel and keeps its own for last).  With several contexts on one GPU, one per
+ * emulated rank, wired to each other's slots and signals, this runs Algorithm 3 end to end (launch the GEMMs before
+ * the reducers then: the streams of many contexts share the device's few hardware queues, and a GEMM queued behind a
+ * reducer that waits for its signal cannot start until that reducer's time limit).
+ */
+int gemm_rs_scatter(agg_ctx* ctx, int M, int N, int Klocal,
+                    const void* A_local, int lda, const void* B_local, int ldb, int b_layout,
+                    float* const* slice_dst, float* P_other, int32_t* const* slice_signal,
+                    int first_slice, void* gemm_stream);
+
 /* ------------------------------------------------------------------------------------------------
  * MoE AllGather grouped GEMM (Section 4.1 "AllGather MoE", Table 4; tensor parallel).
  * T holds the gathered tokens X[Ttok, K] (shard r = tokens [r*tpr, (r+1)*tpr)).  topk_ids: DEVICE int32

@@ -18,12 +18,11 @@ struct GemmParams {
     const uint16_t* A_local;   // AllGather-GEMM: this rank's own shard where the caller keeps it (nullptr = read it from A)
     int local_lo, local_hi;    // its rows in A
     const uint16_t* B;
-    void* C;              // rows outside [own_lo, own_hi) (or every row if C_own == nullptr)
-    void* C_own;          // GEMM-RS: rows [own_lo, own_hi) go here, at row index (row - own_lo)
-    long long lda, ldb, ldc, ldc_own;
+    void* C;              // every row whose slice has no destination of its own
+    long long lda, ldb, ldc;
     int M, N, K;
     int c_is_f32;
-    int c_vec_ok;         // C (and C_own) and their leading dimensions allow 16-byte row-chunk stores
+    int c_vec_ok;         // C, the slice destinations and their leading dimensions allow 16-byte row-chunk stores
     // tile schedule (Section 3.7: rank-rotated order, local shard first)
     int tiles_m, tiles_n;
     int panel_m;          // m-tiles per panel (a panel = the tiles of one shard step)
@@ -38,11 +37,14 @@ struct GemmParams {
     int n_flags;
     long long wait_ticks; // bound of a wait, in wall-clock ticks
     int* err;             // device word: set to 1 when a wait is given up
-    // GEMM-RS producer signal: tiles touching [own_lo, own_hi) count up done_ctr; the last one sets done_flag
-    int own_lo, own_hi;
-    int* done_ctr;
-    int done_target;
-    int* done_flag;
+    // GEMM-RS scatter (n_slices > 0): the rows are cut into slices of slice_rows; slice w is stored at
+    // slice_dst[w] (row index relative to the slice, leading dimension ldc_slice) where that is not null, else in C.
+    // Tiles touching slice w count up slice_ctr[w]; the last one raises slice_flag[w] (where not null).
+    int n_slices, slice_rows;
+    long long ldc_slice;
+    int* slice_ctr;
+    void* slice_dst[kMaxWorld];
+    int* slice_flag[kMaxWorld];
     // grouped (MoE) GEMM only: rows of A are gathered through row_index, tiles come from a table built on the device
     const int* row_index;         // row p of the output reads row row_index[p] of A
     const struct MoeTile* tile_tab;

@@ -101,7 +101,7 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     hipDeviceProp_t prop;
     int khz = 0;
     const size_t sig_bytes = (size_t)n_signals * kSignalStride * sizeof(int);
-    const size_t ctr_bytes = ((size_t)n_signals + 32) * sizeof(int);
+    const size_t ctr_bytes = ((size_t)n_signals + kMaxWorld + 32) * sizeof(int);   // producer counters, then one per GEMM-RS slice
     if ((rc = hip_fail(hipGetDevice(&c->device))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipGetDeviceProperties(&prop, c->device))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device))) != AGG_OK) goto fail;
@@ -406,71 +406,117 @@ int rs_reduce(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int
     return hip_fail(launch_reduce(a, nwg, (hipStream_t)stream));
 }
 
+int gemm_rs_scatter(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, const void* B_local, int ldb,
+                    int b_layout, float* const* slice_dst, float* P_other, int32_t* const* slice_signal,
+                    int first_slice, void* gemm_stream)
+{
+    if (!c || !slice_dst) return AGG_ERR_INVALID_ARG;
+    if (M % c->W != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (first_slice < 0 || first_slice >= c->W) return AGG_ERR_INVALID_ARG;
+    const int W = c->W, Ms = M / W;
+    if (M == 0 || N == 0) return AGG_OK;
+    // every slice needs somewhere to go
+    const void* any_dst = P_other;
+    for (int w = 0; w < W; ++w) {
+        if (!slice_dst[w] && !P_other) return AGG_ERR_INVALID_ARG;
+        if (slice_dst[w] && !aligned16(slice_dst[w])) return AGG_ERR_MISALIGNED;
+        if (slice_signal && slice_signal[w] && reinterpret_cast<uintptr_t>(slice_signal[w]) % 4 != 0) return AGG_ERR_MISALIGNED;
+        if (!any_dst) any_dst = slice_dst[w];
+    }
+    int rc = check_gemm_operands(M, N, Kl, B_local, ldb, b_layout, any_dst, N, AGG_F32);
+    if (rc != AGG_OK) return rc;
+    if (!A_local || lda < Kl) return AGG_ERR_INVALID_ARG;
+    if (lda % 8 != 0 || !aligned16(A_local)) return AGG_ERR_MISALIGNED;
+    if (P_other && !aligned16(P_other)) return AGG_ERR_MISALIGNED;
+
+    GemmParams p{};
+    p.A = (const uint16_t*)A_local;
+    p.B = (const uint16_t*)B_local;
+    p.C = P_other;
+    p.lda = lda;
+    p.ldb = ldb;
+    p.ldc = N;
+    p.M = M;
+    p.N = N;
+    p.K = Kl;
+    p.c_is_f32 = 1;
+    p.c_vec_ok = N % 4 == 0;              // every destination is 16-byte aligned (checked above)
+    p.epoch = c->epoch;
+    p.err = c->err;
+    p.wait_ticks = wait_ticks(c);
+    p.n_slices = W;
+    p.slice_rows = Ms;
+    p.ldc_slice = N;
+    p.slice_ctr = c->counters + c->n_signals;          // W counters of their own, after the producer's
+    for (int w = 0; w < W; ++w) {
+        p.slice_dst[w] = slice_dst[w];
+        p.slice_flag[w] = slice_signal ? slice_signal[w] : nullptr;
+    }
+    const int cfg = choose_tile(c, M, N);
+    fill_schedule(p, cfg, Ms, first_slice * Ms);
+    const long long tiles = (long long)p.tiles_m * p.tiles_n;
+    const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
+    return hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)gemm_stream));
+}
+
 int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, const void* B_local, int ldb, int b_layout,
             const float* const* slots, float* P_other, void* R, int ldr, int r_dtype, void* gemm_stream,
             void* reduce_stream)
 {
     if (!c || !slots) return AGG_ERR_INVALID_ARG;
     if (M % c->W != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
-    const int Ms = M / c->W;
+    const int W = c->W, Ms = M / W;
     if (M == 0 || N == 0) return AGG_OK;
     if (!slots[c->rank]) return AGG_ERR_INVALID_ARG;
-    int rc = check_gemm_operands(M, N, Kl, B_local, ldb, b_layout, slots[c->rank], N, AGG_F32);
-    if (rc != AGG_OK) return rc;
-    if (!A_local || lda < Kl) return AGG_ERR_INVALID_ARG;
-    if (lda % 8 != 0 || !aligned16(A_local)) return AGG_ERR_MISALIGNED;
     // validate the reduction's arguments before anything is enqueued
     if (!R || ldr < N || (r_dtype != AGG_BF16 && r_dtype != AGG_F32)) return AGG_ERR_INVALID_ARG;
     if (((long long)Ms * N) % 4 != 0 || (ldr != N && N % 4 != 0)) return AGG_ERR_UNSUPPORTED_SHAPE;
-    for (int w = 0; w < c->W; ++w)
+    for (int w = 0; w < W; ++w)
         if (!slots[w] || !aligned16(slots[w])) return slots[w] ? AGG_ERR_MISALIGNED : AGG_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(R) % (4 * (r_dtype == AGG_F32 ? 4 : 2)) != 0 || (ldr != N && ldr % 4 != 0))
         return AGG_ERR_MISALIGNED;
 
-    const int own_lo = c->rank * Ms, own_hi = own_lo + Ms;
-    GemmParams p{};
-    p.B = (const uint16_t*)B_local;
-    p.lda = lda;
-    p.ldb = ldb;
-    p.N = N;
-    p.K = Kl;
-    p.c_is_f32 = 1;
-    p.c_vec_ok = aligned16(slots[c->rank]) && (!P_other || aligned16(P_other)) && N % 4 == 0;
-    p.epoch = c->epoch;
-    p.err = c->err;
-    p.wait_ticks = wait_ticks(c);
-    int cfg;
+    int32_t* own_flag = c->signals + (size_t)c->rank * (c->n_signals / W) * kSignalStride;
+    int rc;
     if (P_other) {
-        p.A = (const uint16_t*)A_local;
-        p.M = M;
-        p.C = P_other;
-        p.ldc = N;
-        p.C_own = (void*)slots[c->rank];
-        p.ldc_own = N;
-        p.own_lo = own_lo;
-        p.own_hi = own_hi;
-        cfg = choose_tile(c, M, N);
-        fill_schedule(p, cfg, Ms, own_lo);
+        // all M rows: the own slice first and straight into its slot, the others' rows into P_other
+        float* dst[kMaxWorld] = {nullptr};
+        int32_t* sig[kMaxWorld] = {nullptr};
+        dst[c->rank] = const_cast<float*>(slots[c->rank]);
+        sig[c->rank] = own_flag;
+        rc = gemm_rs_scatter(c, M, N, Kl, A_local, lda, B_local, ldb, b_layout, dst, P_other, sig, c->rank, gemm_stream);
     } else {
-        p.A = (const uint16_t*)A_local + (long long)own_lo * lda;
-        p.M = Ms;
+        // only the own slice is wanted: a GEMM over its Ms rows, seen as a world of one slice
+        rc = check_gemm_operands(Ms, N, Kl, B_local, ldb, b_layout, slots[c->rank], N, AGG_F32);
+        if (rc != AGG_OK) return rc;
+        if (!A_local || lda < Kl) return AGG_ERR_INVALID_ARG;
+        if (lda % 8 != 0 || !aligned16(A_local)) return AGG_ERR_MISALIGNED;
+        GemmParams p{};
+        p.A = (const uint16_t*)A_local + (long long)c->rank * Ms * lda;
+        p.B = (const uint16_t*)B_local;
         p.C = (void*)slots[c->rank];
+        p.lda = lda;
+        p.ldb = ldb;
         p.ldc = N;
-        p.own_lo = 0;
-        p.own_hi = Ms;
-        cfg = choose_tile(c, Ms, N);
+        p.M = Ms;
+        p.N = N;
+        p.K = Kl;
+        p.c_is_f32 = 1;
+        p.c_vec_ok = N % 4 == 0;
+        p.epoch = c->epoch;
+        p.err = c->err;
+        p.wait_ticks = wait_ticks(c);
+        p.n_slices = 1;
+        p.slice_rows = Ms;
+        p.ldc_slice = N;
+        p.slice_ctr = c->counters + c->n_signals;
+        p.slice_flag[0] = own_flag;
+        const int cfg = choose_tile(c, Ms, N);
         fill_schedule(p, cfg, Ms, 0);
+        const long long tiles = (long long)p.tiles_m * p.tiles_n;
+        const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
+        rc = hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)gemm_stream));
     }
-    {
-        const TileShape t = tile_shape(cfg);
-        const int lo = p.own_lo / t.bm, hi = (p.own_hi - 1) / t.bm;
-        p.done_target = (hi - lo + 1) * p.tiles_n;
-        p.done_ctr = c->counters + c->n_signals;          // a counter of its own, after the producer's
-        p.done_flag = c->signals + (size_t)c->rank * (c->n_signals / c->W) * kSignalStride;
-    }
-    const long long tiles = (long long)p.tiles_m * p.tiles_n;
-    const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
-    rc = hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)gemm_stream));
     if (rc != AGG_OK) return rc;
     // The reducer waits for this rank's own slot, which the GEMM above produces.  A reducer that spun for that
     // signal inside the kernel could hold the registers the GEMM's workgroups still need to become resident, and
@@ -480,7 +526,7 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
     if (gemm_stream != reduce_stream) {
         bool waited = false;
         if (c->can_wait_value) {
-            waited = hipStreamWaitValue32((hipStream_t)reduce_stream, p.done_flag, (uint32_t)c->epoch, hipStreamWaitValueGte,
+            waited = hipStreamWaitValue32((hipStream_t)reduce_stream, own_flag, (uint32_t)c->epoch, hipStreamWaitValueGte,
                                           0xFFFFFFFFu) == hipSuccess;
             if (!waited) (void)hipGetLastError();
         }

@@ -438,11 +438,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
             asm volatile("" : "+v"(lane_e));     // keeps the address arithmetic below inside the tile loop
             const int row_w = m0 + wave * TM;    // first output row of this wave
             const int n_valid = min(BN, p.N - n0);      // columns of this tile inside the matrix
-            // where a row of the output goes: C, or (GEMM-RS) this rank's own slot; nullptr = not stored
+            // where a row of the output goes: C, or (GEMM-RS) the destination of its slice; nullptr = not stored
             auto row_ptr = [&](int row, int esz) -> char* {
                 if (row >= m_lim) return nullptr;
-                if (p.C_own && row >= p.own_lo && row < p.own_hi)
-                    return (char*)p.C_own + ((long long)(row - p.own_lo) * p.ldc_own + n0) * esz;
+                if (!GROUPED && p.n_slices) {
+                    const int w = row / p.slice_rows;
+                    if (p.slice_dst[w])
+                        return (char*)p.slice_dst[w] + ((long long)(row - w * p.slice_rows) * p.ldc_slice + n0) * esz;
+                }
                 return p.C ? (char*)p.C + ((long long)row * p.ldc + n0) * esz : nullptr;
             };
             auto epilogue = [&](auto tag) {
@@ -475,20 +478,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                         // the same wave wrote and reads: LDS keeps a wave's operations in order.  GRP chunks at a
                         // time: their LDS reads first (independent registers), then their stores.
                         const int row0 = row_w + i * 32;
-                        // the 32 rows go to C, or (GEMM-RS) all to this rank's own slot; a block that straddles
-                        // the slot boundary takes the per-row route
-                        const bool own_all = p.C_own && row0 >= p.own_lo && row0 + 32 <= p.own_hi;
-                        const bool own_none = !p.C_own || row0 + 32 <= p.own_lo || row0 >= p.own_hi;
-                        char* base = own_all ? (char*)p.C_own + ((long long)(row0 - p.own_lo) * p.ldc_own + n0) * esz
-                                             : (p.C ? (char*)p.C + ((long long)row0 * p.ldc + n0) * esz : nullptr);
-                        const unsigned ld_bytes = (unsigned)((own_all ? p.ldc_own : p.ldc) * esz);
+                        // the 32 rows go to C, or (GEMM-RS) to the destination of their slice; a block that
+                        // straddles a slice boundary takes the per-row route
                         const int rows_ok = min(32, m_lim - row0);
+                        bool one_dst = true;          // all rows of the block have one destination matrix
+                        char* base = p.C ? (char*)p.C + ((long long)row0 * p.ldc + n0) * esz : nullptr;
+                        unsigned ld_bytes = (unsigned)(p.ldc * esz);
+                        if (!GROUPED && p.n_slices && rows_ok > 0) {
+                            const int w0 = row0 / p.slice_rows, w1 = (row0 + rows_ok - 1) / p.slice_rows;
+                            one_dst = w0 == w1;
+                            if (one_dst && p.slice_dst[w0]) {
+                                base = (char*)p.slice_dst[w0] + ((long long)(row0 - w0 * p.slice_rows) * p.ldc_slice + n0) * esz;
+                                ld_bytes = (unsigned)(p.ldc_slice * esz);
+                            }
+                        }
                         constexpr int GRP = 7;
                         int r = r_lane, cc = cc_lane;
                         if constexpr ((32 * cpr) % 64 == 0) {
                             // the common case -- all 32 rows inside the matrix (or segment) and bound for one
                             // destination -- has no per-lane conditions at all: every lane moves `iters` chunks
-                            if (base && rows_ok >= 32 && n_valid == BN && (own_all || own_none)) {
+                            if (base && rows_ok >= 32 && n_valid == BN && one_dst) {
                                 static_for<(iters + GRP - 1) / GRP>([&](auto g_c) {
                                     constexpr int it0 = decltype(g_c)::value * GRP;
                                     constexpr int n = (iters - it0 < GRP) ? iters - it0 : GRP;
@@ -529,7 +538,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                             });
                             static_for<n>([&](auto k_c) {
                                 constexpr int k = decltype(k_c)::value;
-                                if (own_all || own_none) {
+                                if (one_dst) {
                                     if (base && rs[k] < rows_ok && ccs[k] < cpr_valid) {
                                         // C is not read again by this kernel: streaming stores keep it from
                                         // displacing the A and B lines that are
@@ -564,16 +573,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
 #ifdef AGG_EXP_TIMING
         const long long ttb = __builtin_readcyclecounter();
 #endif
-        // GEMM-RS: count finished tiles of the own slice; the last one raises the producer signal
-        if (p.done_ctr && m0 < p.own_hi && m0 + BM > p.own_lo) {
-            __builtin_amdgcn_s_waitcnt(0);   // this wave's stores of the tile have reached L2 ...
-            __syncthreads();                 // ... and so have every other wave's, before thread 0 publishes them
-            if (tid == 0) {
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                const int prev = __hip_atomic_fetch_add(p.done_ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-                if (prev == p.done_target - 1) {
-                    __hip_atomic_store(p.done_ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(p.done_flag, p.epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        // GEMM-RS: count this tile for every slice it touches; the last tile of a slice raises the slice's signal
+        // (the notify of Algorithm 3: the slice is complete where its reducer will read it)
+        if (!GROUPED && p.n_slices && p.slice_ctr) {
+            const int w_lo = m0 / p.slice_rows, w_hi = (min(m0 + BM, p.M) - 1) / p.slice_rows;
+            bool any = false;
+            for (int w = w_lo; w <= w_hi; ++w) any = any || p.slice_flag[w] != nullptr;
+            if (any) {
+                __builtin_amdgcn_s_waitcnt(0);   // this wave's stores of the tile have reached L2 ...
+                __syncthreads();                 // ... and so have every other wave's, before thread 0 publishes them
+                if (tid == 0) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                    for (int w = w_lo; w <= w_hi; ++w) {
+                        if (!p.slice_flag[w]) continue;
+                        // tiles that touch slice w: its m-tiles times all n-tiles
+                        const int mt_lo = (w * p.slice_rows) / BM, mt_hi = (min((w + 1) * p.slice_rows, p.M) - 1) / BM;
+                        const int target = (mt_hi - mt_lo + 1) * p.tiles_n;
+                        const int prev = __hip_atomic_fetch_add(p.slice_ctr + w, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+                        if (prev == target - 1) {
+                            __hip_atomic_store(p.slice_ctr + w, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __hip_atomic_store(p.slice_flag[w], p.epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
                 }
             }
         }

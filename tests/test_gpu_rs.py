@@ -246,3 +246,93 @@ def test_gemm_rs_full_size_sampled_rows():
     rows_other = np.sort(rng.choice(np.setdiff1d(np.arange(sh.M), np.arange(rank * sh.Ms, (rank + 1) * sh.Ms)),
                                     size=12, replace=False))
     _gemm_rs_case(sh, rank, rows_own, rows_other, orders=2)
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# Algorithm 3 end to end: W emulated ranks on one GPU, each scattering its partial slices into the others' slots
+# ----------------------------------------------------------------------------------------------------------------
+
+def _all_ranks_gemm_rs(shape, reducers_first, tile=None, rows=None):
+    import dataclasses
+    W, M, Ms, Kl, N = shape.W, shape.M, shape.Ms, shape.Kl, shape.N
+    inputs = [wl.make_gemm_rs(dataclasses.replace(shape, cfg=shape.cfg + 20 + r), rank=r) for r in range(W)]
+    A = [dev_bf16(i.A_loc) for i in inputs]
+    B = [dev_bf16(np.ascontiguousarray(i.B_kn.T)) for i in inputs]
+    ranks = [RsRun(W, r, Ms, N) for r in range(W)]             # slots[r][w]: rank r's slot for peer w, poisoned
+    R = [torch.full((Ms, N), float("nan"), device="cuda", dtype=torch.float32) for _ in range(W)]
+    try:
+        for rr in ranks:
+            if tile is not None:
+                rr.ctx.set_tile_config(tile)
+            agg.signal_reset(rr.ctx)
+        torch.cuda.synchronize()
+
+        def reducers():
+            for r, rr in enumerate(ranks):
+                agg.rs_reduce(rr.ctx, Ms, N, rr.slots, R[r], N, agg.F32, 0, rr.cons)
+
+        def gemms():
+            for w, rw in enumerate(ranks):                     # rank w computes P_w and scatters slice r to rank r
+                dst = [ranks[r].slots[w] for r in range(W)]
+                sig = [ranks[r].ctx.signals + (w * ranks[r].step) * agg.SIGNAL_STRIDE * 4 for r in range(W)]
+                # start with the slice of the next rank, the own slice last (it does not have to travel)
+                agg.gemm_rs_scatter(rw.ctx, M, N, Kl, A[w], Kl, B[w], Kl, agg.B_NK, dst, None, sig, (w + 1) % W, rw.prod)
+
+        if reducers_first:
+            reducers(); gemms()
+        else:
+            gemms(); reducers()
+        for rr in ranks:
+            rr.status_ok()
+        # each rank's result is the ordered fp32 sum of what landed in its slots, bit for bit ...
+        for r, rr in enumerate(ranks):
+            slots = [s.cpu().numpy() for s in rr.slots]
+            assert not any(np.isnan(s).any() for s in slots)
+            assert np.array_equal(oracle.rs_reduce_f32(slots).view(np.uint32), R[r].cpu().numpy().view(np.uint32))
+        # ... and all of them together are one GEMM over the concatenated K (the definition of GEMM + ReduceScatter)
+        A_cat = np.concatenate([i.A_loc for i in inputs], axis=1)
+        B_cat = np.concatenate([i.B_kn for i in inputs], axis=0)
+        got = torch.cat(R).cpu().numpy().astype(np.float64)
+        rows = np.arange(M) if rows is None else rows
+        want = oracle.gemm(A_cat, B_cat, rows=rows)
+        g = got[rows]
+        rel = np.linalg.norm(g - want) / np.linalg.norm(want)
+        assert rel <= 1e-4, rel
+        assert np.abs(g - want).max() <= 1e-3 * np.sqrt(W * Kl) * max(1.0, float(np.abs(want).max()))
+    finally:
+        for rr in ranks:
+            rr.close()
+
+
+@pytest.mark.parametrize("tile", [0, 1])
+def test_all_ranks_on_one_gpu_tiny(tile):
+    # The GEMMs are launched before the reducers: eight streams share the device's few hardware queues, and a GEMM
+    # queued behind a reducer that waits for that very GEMM's signal could not start.
+    _all_ranks_gemm_rs(wl.RS_TINY, reducers_first=False, tile=tile)
+
+
+def test_all_ranks_on_one_gpu_medium():
+    sh = wl.GemmRsShape("gemm_rs_medium", 13, 4, 2048, 512, 1024)
+    rows = np.sort(np.random.default_rng(2).choice(sh.M, size=64, replace=False))
+    _all_ranks_gemm_rs(sh, reducers_first=False, rows=rows)
+
+
+def test_gemm_rs_scatter_argument_errors():
+    sh = wl.RS_TINY
+    run = RsRun(sh.W, 0, sh.Ms, sh.N)
+    try:
+        inp = wl.make_gemm_rs(sh, rank=0)
+        A, B = dev_bf16(inp.A_loc), dev_bf16(np.ascontiguousarray(inp.B_kn.T))
+        good = dict(M=sh.M, N=sh.N, K=sh.Kl, dst=run.slots, P=None, sig=None, first=0)
+        def call(**kw):
+            a = dict(good); a.update(kw)
+            agg.gemm_rs_scatter(run.ctx, a["M"], a["N"], a["K"], A, sh.Kl, B, sh.Kl, agg.B_NK, a["dst"], a["P"], a["sig"],
+                                a["first"], run.prod)
+        for bad in (dict(first=sh.W), dict(first=-1), dict(M=sh.M + 1), dict(dst=run.slots[:3] + [None]), dict(K=sh.Kl + 8)):
+            with pytest.raises(agg.AggError):
+                call(**bad)
+        call(N=0)                       # empty: a no-op
+        call()
+        run.status_ok()
+    finally:
+        run.close()
