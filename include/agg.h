@@ -164,6 +164,25 @@ int gemm_rs(agg_ctx* ctx, int M, int N, int Klocal,
             void* R, int ldr, int r_dtype, void* gemm_stream, void* reduce_stream);
 
 /*
+ * Tuning (Section 3.8, the autotuner for overlapped kernels).  What is timed is the whole overlapped function:
+ * signal_reset, ag_producer_emulate (rotated arrival order) on the context's producer stream, ag_gemm on its consumer
+ * stream, join -- with the signals reset before every run, never a kernel repeated on its own.  Candidates: both tile
+ * shapes x both tile orders x three producer sizes (half, one and two workgroups per compute unit; one candidate
+ * when the copy engines are used).  Each candidate runs once to warm up and runs_per_config more times; the
+ * fastest single run counts.  The best configuration is stored in the context (tile shape, tile order, producer
+ * size used when ag_producer_emulate is called with n_workgroups = 0) and returned.  Synchronous.  On one GPU
+ * there is no agreement between ranks to reach; on a node the ranks would exchange *out and take the slowest
+ * rank's best.  C is overwritten.  Any error leaves the context's settings as they were.
+ */
+typedef struct agg_tune_result {
+    int tile_config, tile_order, producer_workgroups, configs_tried;
+    float best_ms;
+} agg_tune_result;
+int agg_autotune_ag_gemm(agg_ctx* ctx, int M, int N, int K, const void* B, int ldb, int b_layout,
+                         void* C, int ldc, int c_dtype, const void* const* remote_shards, int producer_mode,
+                         int runs_per_config, agg_tune_result* out);
+
+/*
  * The GEMM half of GEMM + ReduceScatter with the scatter fused into its epilogue (Section 3.6, "Intra-node
  * ReduceScatter with Fusion"; Algorithm 3, stream 1): P[M, N] = A_local[M, Klocal] . B_local in fp32, cut into W row
  * slices of M / W rows.  Slice w is stored straight into slice_dst[w] (HOST array of W DEVICE pointers, each fp32

@@ -12,7 +12,7 @@ import os
 
 __all__ = [
     "AggError", "Ctx", "symm_alloc", "signal_reset", "signal_set", "ag_producer_emulate", "ag_gemm",
-    "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
+    "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "agg_autotune_ag_gemm", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
     "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL", "PRODUCER_LOCAL_LAST",
     "ORDER_ROTATED", "ORDER_SUBCHUNK", "SIGNAL_STRIDE",
     "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM",
@@ -29,7 +29,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT
 # every symbol include/agg.h declares
 EXPORTS = [
     "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
-    "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs", "gemm_rs_scatter",
+    "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs", "gemm_rs_scatter", "agg_autotune_ag_gemm",
     "ag_moe_gemm", "agg_set_tile_config", "agg_set_tile_order", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
 ]
 
@@ -73,6 +73,7 @@ def _lib() -> C.CDLL:
         L.rs_reduce.argtypes = [vp, i32, i32, C.POINTER(vp), vp, i32, i32, i32, vp]
         L.gemm_rs.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32, i32, C.POINTER(vp), vp, vp, i32, i32, vp, vp]
         L.gemm_rs_scatter.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32, i32, C.POINTER(vp), vp, C.POINTER(vp), i32, vp]
+        L.agg_autotune_ag_gemm.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, i32, i32, C.POINTER(vp), i32, i32, vp]
         L.ag_moe_gemm.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32, vp]
         L.agg_strerror.argtypes = [i32]
         L.agg_strerror.restype = C.c_char_p
@@ -232,6 +233,20 @@ def gemm_rs_scatter(ctx: Ctx, M: int, N: int, Klocal: int, A_local, lda: int, B_
     _check(_lib().gemm_rs_scatter(ctx.handle, M, N, Klocal, _ptr(A_local), lda, _ptr(B_local), ldb, b_layout,
                                   _ptr_array(slice_dst), _ptr(P_other), sig, first_slice, _stream(gemm_stream)),
            "gemm_rs_scatter")
+
+
+class TuneResult(C.Structure):
+    _fields_ = [("tile_config", C.c_int), ("tile_order", C.c_int), ("producer_workgroups", C.c_int),
+                ("configs_tried", C.c_int), ("best_ms", C.c_float)]
+
+
+def agg_autotune_ag_gemm(ctx: Ctx, M: int, N: int, K: int, B, ldb: int, b_layout: int, Cout, ldc: int, c_dtype: int,
+                         remote_shards, producer_mode: int = PRODUCER_KERNEL, runs_per_config: int = 3) -> TuneResult:
+    res = TuneResult()
+    _check(_lib().agg_autotune_ag_gemm(ctx.handle, M, N, K, _ptr(B), ldb, b_layout, _ptr(Cout), ldc, c_dtype,
+                                       _ptr_array(remote_shards), producer_mode, runs_per_config, C.byref(res)),
+           "agg_autotune_ag_gemm")
+    return res
 
 
 def ag_moe_gemm(ctx: Ctx, Ttok: int, topk: int, E: int, N: int, K: int, topk_ids, weights, sorted_token,

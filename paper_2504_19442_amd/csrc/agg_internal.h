@@ -140,6 +140,7 @@ struct agg_ctx {
     int device;
     int tile_config;     // -1 = automatic
     int tile_order;      // AGG_ORDER_*
+    int producer_wgs;    // workgroups of the producer kernel when the caller passes 0 (0 = one per CU)
     const void* local_shard;  // see agg_set_local_shard
     double link_GBps;    // pace of a link of the full-mesh producer (0 = not paced)
     hipStream_t producer_stream, consumer_stream;

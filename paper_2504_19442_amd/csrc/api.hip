@@ -268,12 +268,12 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     a.epoch = c->epoch;
     hipStream_t st = (hipStream_t)producer_stream;
     if (mode == AGG_PRODUCER_KERNEL) {
-        const int nwg = n_workgroups > 0 ? n_workgroups : c->num_cus;
+        const int nwg = n_workgroups > 0 ? n_workgroups : (c->producer_wgs > 0 ? c->producer_wgs : c->num_cus);
         return hip_fail(launch_producer(a, nwg, st));
     }
     if (mode == AGG_PRODUCER_LINKS) {
         // the local copy first, at full width (it crosses no link); then every peer on a link of its own
-        const int nwg = n_workgroups > 0 ? n_workgroups : c->num_cus;
+        const int nwg = n_workgroups > 0 ? n_workgroups : (c->producer_wgs > 0 ? c->producer_wgs : c->num_cus);
         const bool has_local = !skip_local;
         const int first_remote = (has_local && !local_last) ? 1 : 0;
         const int local_job = local_last ? a.n_jobs - 1 : 0;
@@ -404,6 +404,77 @@ int rs_reduce(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int
         if (nwg < 1) nwg = 1;
     }
     return hip_fail(launch_reduce(a, nwg, (hipStream_t)stream));
+}
+
+// Tuning in the manner of Section 3.8: the unit that is timed is the whole overlapped function -- reset of the
+// signals, arrival on the producer stream, gated GEMM on the consumer stream, join -- never a kernel on its own, whose
+// waits would find the signals of the previous run.  One candidate configuration per run of the function.
+int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layout, void* C, int ldc,
+                         int c_dtype, const void* const* remote_shards, int producer_mode, int runs_per_config,
+                         agg_tune_result* out)
+{
+    if (!c || !out || runs_per_config < 1 || runs_per_config > 1000) return AGG_ERR_INVALID_ARG;
+    const int saved_tile = c->tile_config, saved_order = c->tile_order, saved_wgs = c->producer_wgs;
+    const int tiles[2] = {TILE_256x224, TILE_128x128};
+    const int orders[2] = {AGG_ORDER_ROTATED, AGG_ORDER_SUBCHUNK};
+    const int wgs[3] = {c->num_cus / 2 > 0 ? c->num_cus / 2 : 1, c->num_cus, 2 * c->num_cus};
+    hipEvent_t e0 = nullptr, e1 = nullptr, join = nullptr;
+    int rc = AGG_OK;
+    float best = 1e30f;
+    agg_tune_result res{};
+    if ((rc = hip_fail(hipEventCreate(&e0))) != AGG_OK) return rc;
+    if ((rc = hip_fail(hipEventCreate(&e1))) != AGG_OK) { (void)hipEventDestroy(e0); return rc; }
+    if ((rc = hip_fail(hipEventCreateWithFlags(&join, hipEventDisableTiming))) != AGG_OK) {
+        (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return rc;
+    }
+    const bool sdma = (producer_mode & 0xff) == AGG_PRODUCER_SDMA;
+    for (int ti = 0; ti < 2 && rc == AGG_OK; ++ti)
+        for (int oi = 0; oi < 2 && rc == AGG_OK; ++oi)
+            for (int wi = 0; wi < (sdma ? 1 : 3) && rc == AGG_OK; ++wi) {
+                c->tile_config = tiles[ti];
+                c->tile_order = orders[oi];
+                c->producer_wgs = wgs[wi];
+                float best_here = 1e30f;
+                for (int it = 0; it < runs_per_config + 1 && rc == AGG_OK; ++it) {      // the first run warms up
+                    if ((rc = signal_reset(c, nullptr)) != AGG_OK) break;
+                    // fork: both streams start from the same point
+                    if ((rc = hip_fail(hipEventRecord(e0, c->consumer_stream))) != AGG_OK) break;
+                    if ((rc = hip_fail(hipStreamWaitEvent(c->producer_stream, e0, 0))) != AGG_OK) break;
+                    if ((rc = ag_producer_emulate(c, remote_shards, nullptr, 0, producer_mode, 0, c->producer_stream)) != AGG_OK) break;
+                    if ((rc = ag_gemm(c, M, N, K, B, ldb, b_layout, C, ldc, c_dtype, c->consumer_stream)) != AGG_OK) break;
+                    // join: the function is over when both parts are
+                    if ((rc = hip_fail(hipEventRecord(join, c->producer_stream))) != AGG_OK) break;
+                    if ((rc = hip_fail(hipStreamWaitEvent(c->consumer_stream, join, 0))) != AGG_OK) break;
+                    if ((rc = hip_fail(hipEventRecord(e1, c->consumer_stream))) != AGG_OK) break;
+                    if ((rc = hip_fail(hipEventSynchronize(e1))) != AGG_OK) break;
+                    float ms = 0.f;
+                    if ((rc = hip_fail(hipEventElapsedTime(&ms, e0, e1))) != AGG_OK) break;
+                    if (it > 0 && ms < best_here) best_here = ms;
+                }
+                if (rc == AGG_OK) rc = agg_status(c);          // a candidate whose waits time out is an error, not a result
+                ++res.configs_tried;
+                if (rc == AGG_OK && best_here < best) {
+                    best = best_here;
+                    res.tile_config = tiles[ti];
+                    res.tile_order = orders[oi];
+                    res.producer_workgroups = sdma ? 0 : wgs[wi];
+                    res.best_ms = best_here;
+                }
+            }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipEventDestroy(join);
+    if (rc != AGG_OK) {
+        c->tile_config = saved_tile;
+        c->tile_order = saved_order;
+        c->producer_wgs = saved_wgs;
+        return rc;
+    }
+    c->tile_config = res.tile_config;
+    c->tile_order = res.tile_order;
+    c->producer_wgs = res.producer_workgroups;
+    *out = res;
+    return AGG_OK;
 }
 
 int gemm_rs_scatter(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, const void* B_local, int ldb,

@@ -364,3 +364,28 @@ def run_plain(run, tile):
     out = run.run(tile=tile).cpu().numpy()
     run.ctx.set_local_shard(run.remote[run.rank])
     return out
+
+
+def test_autotuner_runs_the_whole_function_and_leaves_a_working_configuration():
+    inp = wl.make_ag_gemm(MESH_SHAPE)
+    sh = MESH_SHAPE
+    want = oracle.ag_gemm(inp.shards, inp.B_kn, 1)
+    run = AgGemmRun(inp, 1, chunks_per_shard=2)
+    try:
+        C = torch.zeros((sh.M, sh.N), device="cuda", dtype=torch.float32)
+        e_before = run.ctx.epoch
+        res = agg.agg_autotune_ag_gemm(run.ctx, sh.M, sh.N, sh.K, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.remote,
+                                       agg.PRODUCER_KERNEL, 2)
+        assert res.configs_tried == 12 and res.tile_config in (0, 1) and res.tile_order in (0, 1)
+        assert res.producer_workgroups > 0 and 0.0 < res.best_ms < 1000.0
+        assert run.ctx.epoch == e_before + 12 * 3          # the signals were reset before every single run
+        check_f32(C.cpu().numpy(), want, sh.K)              # the last tuning run left a complete, correct C
+        check_f32(run.run().cpu().numpy(), want, sh.K)      # and the chosen configuration works
+        res2 = agg.agg_autotune_ag_gemm(run.ctx, sh.M, sh.N, sh.K, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.remote,
+                                        agg.PRODUCER_SDMA, 1)
+        assert res2.configs_tried == 4 and res2.producer_workgroups == 0
+        with pytest.raises(agg.AggError):
+            agg.agg_autotune_ag_gemm(run.ctx, sh.M, sh.N, sh.K + 8, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.remote,
+                                     agg.PRODUCER_KERNEL, 1)
+    finally:
+        run.close()
