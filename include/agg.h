@@ -168,8 +168,8 @@ int gemm_rs(agg_ctx* ctx, int M, int N, int Klocal,
  * signal_reset, ag_producer_emulate (rotated arrival order) on the context's producer stream, ag_gemm on its consumer
  * stream, join -- with the signals reset before every run, never a kernel repeated on its own.  Candidates: both tile
  * shapes x both tile orders x three producer sizes (half, one and two workgroups per compute unit; one candidate
- * when the copy engines are used).  Each candidate runs once to warm up and runs_per_config more times; the
- * fastest single run counts.  The best configuration is stored in the context (tile shape, tile order, producer
+ * when the copy engines are used).  Each candidate runs once to warm up (the very first thirty times, so that the
+ * chip's clocks have settled) and runs_per_config more times; the median run counts.  The best configuration is stored in the context (tile shape, tile order, producer
  * size used when ag_producer_emulate is called with n_workgroups = 0) and returned.  Synchronous.  On one GPU
  * there is no agreement between ranks to reach; on a node the ranks would exchange *out and take the slowest
  * rank's best.  C is overwritten.  Any error leaves the context's settings as they were.

@@ -2,6 +2,9 @@
 // method happens on the host; every step runs in the HIP kernels of this library.
 #include "agg_internal.h"
 
+#include <algorithm>
+#include <vector>
+
 #include <new>
 
 using namespace agg;
@@ -434,8 +437,11 @@ int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb
                 c->tile_config = tiles[ti];
                 c->tile_order = orders[oi];
                 c->producer_wgs = wgs[wi];
-                float best_here = 1e30f;
-                for (int it = 0; it < runs_per_config + 1 && rc == AGG_OK; ++it) {      // the first run warms up
+                std::vector<float> times;
+                // untimed runs first: one per candidate, and a longer series before the very first candidate, so
+                // that the chip's clocks have settled under load before anything is compared
+                const int warm = res.configs_tried == 0 ? 30 : 1;
+                for (int it = 0; it < runs_per_config + warm && rc == AGG_OK; ++it) {
                     if ((rc = signal_reset(c, nullptr)) != AGG_OK) break;
                     // fork: both streams start from the same point
                     if ((rc = hip_fail(hipEventRecord(e0, c->consumer_stream))) != AGG_OK) break;
@@ -449,7 +455,12 @@ int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb
                     if ((rc = hip_fail(hipEventSynchronize(e1))) != AGG_OK) break;
                     float ms = 0.f;
                     if ((rc = hip_fail(hipEventElapsedTime(&ms, e0, e1))) != AGG_OK) break;
-                    if (it > 0 && ms < best_here) best_here = ms;
+                    if (it >= warm) times.push_back(ms);
+                }
+                float best_here = 1e30f;
+                if (!times.empty()) {
+                    std::sort(times.begin(), times.end());
+                    best_here = times[times.size() / 2];       // the median run
                 }
                 if (rc == AGG_OK) rc = agg_status(c);          // a candidate whose waits time out is an error, not a result
                 ++res.configs_tried;
