@@ -225,6 +225,11 @@ def test_full_size_sampled_rows_and_order_invariance(shape, n_orders):
                 assert np.array_equal(C16, want)
             else:
                 assert np.array_equal(C16, base16), f"arrival order {order} changed the output bits"
+        # the configuration the benchmark times: own shard read in place, its copy into T last, producer launched first
+        run.ctx.set_local_shard(run.remote[rank])
+        C16 = host_bits(run.run(None, out_dtype=agg.BF16, mode=agg.PRODUCER_KERNEL | agg.PRODUCER_LOCAL_LAST,
+                                consumer_first=False))
+        assert np.array_equal(C16, base16)
     finally:
         run.close()
 
