@@ -150,9 +150,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
     else if constexpr (C_::ACC == 128) asm volatile("; accumulators a0..a127" ::: "a127");
     else asm volatile("; accumulators a0..a63" ::: "a63");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-#ifdef AGG_EXP_PRIO
-    __builtin_amdgcn_s_setprio(AGG_EXP_PRIO);
-#endif
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -176,9 +173,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
     const int g = blockIdx.x;
     const int xcd_slots = G >> 3;        // workgroups per XCD when G % 8 == 0
 
-#ifdef AGG_EXP_STAGGER
-    for (int d = 0; d < (g & 7) * AGG_EXP_STAGGER; ++d) __builtin_amdgcn_s_sleep(16);
-#endif
     for (int base = 0; base < total_tiles; base += G) {
         // ---- which tile: consecutive tiles of the list go to the workgroups of one XCD
         int t;
