@@ -394,3 +394,18 @@ def test_autotuner_runs_the_whole_function_and_leaves_a_working_configuration():
                                      agg.PRODUCER_KERNEL, 1)
     finally:
         run.close()
+
+
+@pytest.mark.parametrize("K", [64, 192, 448, 960])
+def test_short_and_odd_k_ranges(K):
+    """One to fifteen stages of 64: fewer than the ring holds, fewer than one unrolled pass of the main loop, more."""
+    sh = wl.AgGemmShape(f"ag_k{K}", 14, 2, 136, K, 232)
+    inp = wl.make_ag_gemm(sh, a_dist=("int", 2), b_dist=("int", 2))
+    want = oracle.ag_gemm(inp.shards, inp.B_kn, 1)
+    run = AgGemmRun(inp, 1)
+    try:
+        for tile in (0, 1):
+            C = run.run(tile=tile).cpu().numpy()
+            assert np.array_equal(C.astype(np.float64), want), (K, tile)      # integer inputs: exact
+    finally:
+        run.close()
