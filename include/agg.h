@@ -70,11 +70,12 @@ int symm_epoch(agg_ctx* ctx);                /* current epoch (host value) */
 
 /*
  * Two streams the context owns, for the communication part and the computation part (Section 2.3: the host
- * "launches the communication part and the computation part on different streams").  They are created
- * back to back at symm_alloc so that they sit on different hardware queues: kernels of streams that share
- * a hardware queue run one after the other, and a consumer launched ahead of its producer on such a pair
- * would wait for signals that cannot come (its waits are bounded, so it would time out, not hang).
- * Callers may use streams of their own instead; then they should launch the producer first.
+ * "launches the communication part and the computation part on different streams").  Kernels of streams that
+ * share a hardware queue run one after the other, and a consumer launched ahead of its producer on such a pair
+ * would wait for signals that cannot come (its waits are bounded, so it would time out, not hang).  Which queue
+ * a stream gets cannot be chosen, so symm_alloc tries it out: it keeps the first of up to eight new streams on
+ * which a one-thread kernel gets through while a one-thread kernel on the consumer stream is still waiting for it
+ * (at most 0.5 ms per try).  Callers may use streams of their own instead; then they should launch the producer first.
  */
 int symm_streams(agg_ctx* ctx, void** producer_stream, void** consumer_stream);
 

@@ -104,6 +104,7 @@ struct ProducerArgs {
 hipError_t launch_producer(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_producer_links(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_signal_set(int* flag, int value, hipStream_t stream);
+hipError_t launch_signal_probe(const int* flag, int value, long long ticks, int* seen, hipStream_t stream);
 
 struct ReduceArgs {
     const float* slot[kMaxWorld];

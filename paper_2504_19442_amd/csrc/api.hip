@@ -82,6 +82,39 @@ int check_gemm_operands(int M, int N, int K, const void* B, int ldb, int b_layou
     return AGG_OK;
 }
 
+// The producer stream must run side by side with the consumer stream: streams that the runtime has put on one
+// hardware queue run their kernels one after the other.  Which queue a new stream gets cannot be asked for, so it
+// is tried out: a one-thread kernel on the consumer stream waits (for at most 0.5 ms) for a word that a one-thread
+// kernel on the candidate stream sets.  The first candidate whose kernel gets through while the other still waits
+// is kept.  If none of eight does, the last one is kept: the library then still works when the producer is launched
+// first, as the interface asks of callers with streams of their own.
+int pick_concurrent_stream(agg_ctx* c)
+{
+    constexpr int kTries = 8;
+    hipStream_t cand[kTries] = {nullptr};
+    int* word = c->err + 32;              // two words of the context's bookkeeping block
+    int rc = AGG_OK, chosen = -1, made = 0;
+    for (int i = 0; i < kTries && chosen < 0; ++i) {
+        if ((rc = hip_fail(hipStreamCreateWithFlags(&cand[i], hipStreamNonBlocking))) != AGG_OK) break;
+        made = i + 1;
+        if ((rc = hip_fail(hipMemset(word, 0, 2 * sizeof(int)))) != AGG_OK) break;
+        if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) break;
+        if ((rc = hip_fail(launch_signal_probe(word, 1, c->wall_khz / 2, word + 1, c->consumer_stream))) != AGG_OK) break;
+        if ((rc = hip_fail(launch_signal_set(word, 1, cand[i]))) != AGG_OK) break;
+        if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) break;
+        int seen = 0;
+        if ((rc = hip_fail(hipMemcpy(&seen, word + 1, sizeof seen, hipMemcpyDeviceToHost))) != AGG_OK) break;
+        if (seen == 1) chosen = i;
+    }
+    if (rc == AGG_OK && chosen < 0) chosen = made - 1;
+    for (int i = 0; i < made; ++i)
+        if (i != chosen || rc != AGG_OK) (void)hipStreamDestroy(cand[i]);
+    if (rc != AGG_OK) return rc;
+    c->producer_stream = cand[chosen];
+    (void)hipMemset(word, 0, 2 * sizeof(int));
+    return AGG_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -113,6 +146,9 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     {
         int can = 0;
         if (hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, c->device) != hipSuccess) (void)hipGetLastError();
+#ifdef AGG_EXP_NO_WAITVALUE
+        can = 0;
+#endif
         c->can_wait_value = can;
     }
     if ((rc = hip_fail(hipMalloc((void**)&c->staging, (size_t)world_size * shard_bytes))) != AGG_OK) goto fail;
@@ -124,8 +160,8 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     if ((rc = hip_fail(hipMemset(c->counters, 0, ctr_bytes))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMemset(c->err, 0, 256))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMemset(c->epoch_word, 0, 256))) != AGG_OK) goto fail;
-    if ((rc = hip_fail(hipStreamCreateWithFlags(&c->producer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipStreamCreateWithFlags(&c->consumer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
+    if ((rc = pick_concurrent_stream(c)) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipEventCreateWithFlags(&c->gemm_done, hipEventDisableTiming))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) goto fail;
     *out = c;

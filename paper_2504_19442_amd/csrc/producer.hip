@@ -159,6 +159,25 @@ hipError_t launch_producer_links(const ProducerArgs& a_in, int n_workgroups, hip
     return hipGetLastError();
 }
 
+// One thread waits (for at most `ticks` of the wall clock) until *flag >= value and writes what it saw to *seen:
+// 1 = the value arrived, 2 = the wait ran out.  Used to find out whether two streams really run side by side.
+__global__ void signal_probe_kernel(const int* flag, int value, long long ticks, int* seen)
+{
+    const long long t0 = wall_clock64();
+    int ok = 0;
+    while (!(ok = __hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= value)) {
+        if (wall_clock64() - t0 > ticks) break;
+        __builtin_amdgcn_s_sleep(8);
+    }
+    __hip_atomic_store(seen, ok ? 1 : 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+hipError_t launch_signal_probe(const int* flag, int value, long long ticks, int* seen, hipStream_t stream)
+{
+    hipLaunchKernelGGL(signal_probe_kernel, dim3(1), dim3(1), 0, stream, flag, value, ticks, seen);
+    return hipGetLastError();
+}
+
 hipError_t launch_signal_set(int* flag, int value, hipStream_t stream)
 {
     hipLaunchKernelGGL(signal_set_kernel, dim3(1), dim3(1), 0, stream, flag, value);
