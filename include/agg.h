@@ -11,7 +11,10 @@
  *
  * Every function returns AGG_OK (0) or a negative AGG_ERR_* code and has no other
  * effect when it fails; agg_strerror names a code.  Functions are not thread-safe
- * on one context; different contexts are independent.
+ * on one context; different contexts are independent.  A context carries one set of
+ * arrival counters, slice counters and tile tables: two producers, two gemm_rs /
+ * gemm_rs_scatter or two ag_moe_gemm launches of ONE context must not be in flight at
+ * the same time (order them on a stream or with events, or use a context each).
  *
  * Vocabulary (the paper's, Section 2.1 and Algorithms 1-3): W = WORLD_SIZE,
  * rank = RANK, T = symmetric buffer, S = signal array, L = a rank's local shard.
