@@ -252,6 +252,15 @@ int agg_set_link_rate(agg_ctx* ctx, double gigabytes_per_second);
 /* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 128x128.  A tuning knob (Section 3.8); every shape gives the same result up to fp32 summation order. */
 int agg_set_tile_config(agg_ctx* ctx, int tile_config);
 
+/*
+ * Measured ceiling for the MFMA roofline: enqueues on `stream` a kernel in which every wave of one workgroup per
+ * compute unit issues `iterations` x 14 v_mfma_f32_32x32x16_bf16 from registers (the GEMM's accumulator pattern, no
+ * memory traffic); *flop receives the floating-point operations of the launch (host value, written at once).  The
+ * caller times it.  constant_operands = 0: pseudo-random operands in the ranges of the benchmark's inputs (what real
+ * data costs in power, hence in clock); 1: every operand element the same (the chip's best case).
+ */
+int agg_mfma_ceiling(agg_ctx* ctx, int iterations, int constant_operands, double* flop, void* stream);
+
 const char* agg_strerror(int code);
 
 /* Device facts the bench reports against (compute units, peak clock in kHz). */

@@ -106,6 +106,8 @@ hipError_t launch_producer_links(const ProducerArgs& a, int n_workgroups, hipStr
 hipError_t launch_signal_set(int* flag, int value, hipStream_t stream);
 hipError_t launch_signal_probe(const int* flag, int value, long long ticks, int* seen, hipStream_t stream);
 
+hipError_t launch_mfma_ceiling(float* sink, int grid, int iters, int constant_operands, hipStream_t stream);
+
 struct ReduceArgs {
     const float* slot[kMaxWorld];
     int W;

@@ -154,11 +154,11 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     if ((rc = hip_fail(hipMalloc((void**)&c->staging, (size_t)world_size * shard_bytes))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMalloc((void**)&c->signals, sig_bytes))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMalloc((void**)&c->counters, ctr_bytes))) != AGG_OK) goto fail;
-    if ((rc = hip_fail(hipMalloc((void**)&c->err, 256))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMalloc((void**)&c->err, 2048))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMalloc((void**)&c->epoch_word, 256))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMemset(c->signals, 0, sig_bytes))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMemset(c->counters, 0, ctr_bytes))) != AGG_OK) goto fail;
-    if ((rc = hip_fail(hipMemset(c->err, 0, 256))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipMemset(c->err, 0, 2048))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipMemset(c->epoch_word, 0, 256))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipStreamCreateWithFlags(&c->consumer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
     if ((rc = pick_concurrent_stream(c)) != AGG_OK) goto fail;
@@ -760,6 +760,15 @@ int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32
     p.a_bytes = (unsigned)a_bytes;
     const int grid = (int)(cap < c->num_cus ? cap : c->num_cus);
     return hip_fail(launch_gemm_grouped(p, cfg, grid, (hipStream_t)stream));
+}
+
+int agg_mfma_ceiling(agg_ctx* c, int iterations, int constant_operands, double* flop, void* stream)
+{
+    if (!c || iterations < 1 || iterations > (1 << 24) || !flop) return AGG_ERR_INVALID_ARG;
+    // one workgroup of four waves per compute unit, 14 MFMAs of 32x32x16 per wave and iteration
+    *flop = (double)c->num_cus * 4.0 * (double)iterations * 14.0 * (2.0 * 32 * 32 * 16);
+    return hip_fail(launch_mfma_ceiling((float*)(c->err + 48), c->num_cus, iterations, constant_operands != 0,
+                                        (hipStream_t)stream));
 }
 
 const char* agg_strerror(int code)
