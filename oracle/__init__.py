@@ -201,5 +201,32 @@ def moe_gemm(shards, W_ekn, topk_ids, rank: int = 0, rows=None) -> np.ndarray:
     return Y
 
 
+def moe_rs(H, W2_ekn, topk_ids, gate, peer_slots: dict, W: int, rank: int, rows=None) -> np.ndarray:
+    """fp64 R for one rank: grouped GEMM on the routed rows H, top-k weighted reduction, plus the peers' slices."""
+    H = _u16(H)
+    W2 = _u16(W2_ekn)
+    ids = np.ascontiguousarray(topk_ids, dtype=np.int32)
+    g = np.ascontiguousarray(gate, dtype=np.float32)
+    T, topk = ids.shape
+    E, Kl, N = W2.shape
+    assert H.shape == (T * topk, Kl) and g.shape == (T, topk) and T % W == 0
+    Tr = T // W
+    arr = []
+    for w in range(W):
+        if w == rank:
+            arr.append(None)
+        else:
+            s_ = np.ascontiguousarray(peer_slots[w])
+            assert s_.dtype == np.float32 and s_.shape == (Tr, N)
+            arr.append(s_)
+    r, rp = _rows(rows)
+    n = Tr if r is None else len(r)
+    R = np.empty((n, N), dtype=np.float64)
+    _check(lib().oracle_moe_rs(C.c_int(W), C.c_int(rank), C.c_int64(T), C.c_int64(Kl), C.c_int64(N), C.c_int(E),
+                               C.c_int(topk), _ptr(H), _ptr(W2), _ptr(ids), _ptr(g), _ptr_array(arr), rp, C.c_int64(n),
+                               _ptr(R)), "moe_rs")
+    return R
+
+
 def rs_required_bandwidth(W: int, link_GBps: float, nic_GBps: float) -> float:
     return float(lib().oracle_rs_required_bandwidth(C.c_int(W), C.c_double(link_GBps), C.c_double(nic_GBps)))

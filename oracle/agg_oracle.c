@@ -340,6 +340,87 @@ done:
 /* -------------------------------------------------- Section 3.5 sizing bound */
 
 /*
+ * MoE + ReduceScatter for one rank (Section 4.1, "MoE ReduceScatter": grouped GEMM, top-k reduction, reduce
+ * scatter; tensor parallel over K), in the order of those three steps:
+ *   Y[p, :]  = H[p, :] . W2_{expert(p)}          for every sorted pair p   (H is [T*topk, Kl], rows in routing order)
+ *   Z[t, :]  = sum_s gate[t, s] * Y[pos(t, s), :]                          (pos = place of pair (t, s) in that order)
+ *   R[i, :]  = Z[rank*Tr + i, :] + sum_{w != rank} slots[w][i, :]          (Tr = T / W tokens per rank)
+ * W2t is [E, Kl, N] bf16 (logical K x N per expert), gate [T, topk] float, slots[w] float [Tr, N] (slots[rank]
+ * unused).  rows selects tokens of the own slice (NULL = all Tr).
+ */
+int oracle_moe_rs(int W, int rank, int64_t T, int64_t Kl, int64_t N, int E, int topk,
+                  const uint16_t* H, const uint16_t* W2t, const int32_t* topk_ids, const float* gate,
+                  const float* const* slots, const int64_t* rows, int64_t n_rows, double* R)
+{
+    if (W < 1 || rank < 0 || rank >= W || T < 0 || T % W != 0 || Kl < 0 || N < 0 || topk < 1 || E < 1)
+        return -1;
+    if (!H || !W2t || !topk_ids || !gate || !slots || !R)
+        return -1;
+    const int64_t Tr = T / W, P = T * topk;
+    if (!rows && n_rows != Tr)
+        return -1;
+    for (int w = 0; w < W; ++w)
+        if (w != rank && !slots[w])
+            return -1;
+    int rc = 0;
+    int32_t* ptok = (int32_t*)malloc(sizeof(int32_t) * (size_t)(P > 0 ? P : 1));
+    int32_t* pslot = (int32_t*)malloc(sizeof(int32_t) * (size_t)(P > 0 ? P : 1));
+    int64_t* pos = (int64_t*)malloc(sizeof(int64_t) * (size_t)(P > 0 ? P : 1));
+    int64_t* seg = (int64_t*)malloc(sizeof(int64_t) * (size_t)(E + 1));
+    if (!ptok || !pslot || !pos || !seg) {
+        rc = -3;
+        goto done;
+    }
+    rc = oracle_moe_route(T, topk, E, topk_ids, ptok, pslot, seg);
+    if (rc)
+        goto done;
+    for (int64_t p = 0; p < P; ++p)
+        pos[(int64_t)ptok[p] * topk + pslot[p]] = p;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t r = rows ? rows[i] : i;
+        if (r < 0 || r >= Tr) {
+            rc = -2;
+            goto done;
+        }
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t r = rows ? rows[i] : i;
+        const int64_t t = (int64_t)rank * Tr + r;
+        double* out = R + i * N;
+        double* y = (double*)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        for (int64_t j = 0; j < N; ++j)
+            out[j] = 0.0;
+        for (int s = 0; s < topk; ++s) {
+            const int64_t p = pos[t * topk + s];
+            const int e = topk_ids[t * topk + s];
+            const uint16_t* w2 = W2t + (size_t)e * Kl * N;
+            for (int64_t j = 0; j < N; ++j)
+                y[j] = 0.0;
+            for (int64_t k = 0; k < Kl; ++k) {                       /* grouped GEMM row */
+                const double a = bf16_bits_to_f64(H[p * Kl + k]);
+                for (int64_t j = 0; j < N; ++j)
+                    y[j] += a * bf16_bits_to_f64(w2[k * N + j]);
+            }
+            const double g = (double)gate[t * topk + s];            /* top-k reduction */
+            for (int64_t j = 0; j < N; ++j)
+                out[j] += g * y[j];
+        }
+        for (int w = 0; w < W; ++w)                                 /* reduce scatter: the peers' partial sums */
+            if (w != rank)
+                for (int64_t j = 0; j < N; ++j)
+                    out[j] += (double)slots[w][r * N + j];
+        free(y);
+    }
+done:
+    free(ptok);
+    free(pslot);
+    free(pos);
+    free(seg);
+    return rc;
+}
+
+/*
  * Bandwidth (GB/s) the local reduction must sustain for perfect overlap in the
  * cross-node ReduceScatter analysis of Section 3.5: with volume B per slice, the
  * intra-node scatter takes (W-1) B / link, the P2P send B / nic, and the

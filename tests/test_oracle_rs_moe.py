@@ -141,3 +141,73 @@ def test_moe_integer_inputs_exact():
     for e in range(sh.E):
         want = X[tok[seg[e]:seg[e + 1]]] @ widen(inp.W_ekn[e]).astype(np.int64)
         assert np.array_equal(Y[seg[e]:seg[e + 1]], want.astype(np.float64))
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# MoE + ReduceScatter (Section 4.1, "MoE ReduceScatter"): grouped GEMM, top-k reduction, reduce scatter
+# ----------------------------------------------------------------------------------------------------------------
+
+def _moe_rs_by_hand(inp, W, rank):
+    """The three steps written out with Python sorting and numpy fp64 products, sharing nothing with the oracle."""
+    sh = inp.shape
+    T, topk = inp.topk_ids.shape
+    pairs = sorted((int(inp.topk_ids[t, s]), t, s) for t in range(T) for s in range(topk))     # (expert, token, slot)
+    pos = {(t, s): p for p, (_, t, s) in enumerate(pairs)}
+    H = wl.bf16_bits_to_f32(inp.H).astype(np.float64)
+    W2 = wl.bf16_bits_to_f32(inp.W2_ekn).astype(np.float64)
+    Tr = T // W
+    R = np.zeros((Tr, sh.N))
+    for i in range(Tr):
+        t = rank * Tr + i
+        for s in range(topk):
+            e = int(inp.topk_ids[t, s])
+            R[i] += float(inp.gate[t, s]) * (H[pos[(t, s)]] @ W2[e])
+        for w in range(W):
+            if w != rank:
+                R[i] += inp.peer_slots[w][i].astype(np.float64)
+    return R
+
+
+@pytest.mark.parametrize("rank", [0, 3])
+def test_moe_rs_oracle_against_steps_written_by_hand(rank):
+    inp = wl.make_moe_rs(wl.MOE_RS_TINY, rank=rank)
+    got = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, inp.peer_slots, wl.MOE_RS_TINY.W, rank)
+    want = _moe_rs_by_hand(inp, wl.MOE_RS_TINY.W, rank)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    rows = np.array([5, 0, 23])
+    sub = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, inp.peer_slots, wl.MOE_RS_TINY.W, rank, rows=rows)
+    assert np.array_equal(sub, got[rows])
+
+
+def test_moe_rs_special_cases():
+    sh = wl.MoeRsShape("t", 17, 2, 6, 64, 8, 3, 2)
+    inp = wl.make_moe_rs(sh, rank=0, h_dist=("int", 2), w_dist=("int", 2))
+    zero = {1: np.zeros((sh.tokens_per_rank, sh.N), dtype=np.float32)}
+    H = wl.bf16_bits_to_f32(inp.H).astype(np.float64)
+    # (1) every expert holds the same matrix: the routing cancels and R = (sum_s gate * H[pos]) . W, one plain product
+    same = np.repeat(inp.W2_ekn[:1], sh.E, axis=0)
+    got = oracle.moe_rs(inp.H, same, inp.topk_ids, inp.gate, zero, sh.W, 0)
+    tok, slot, seg = oracle.moe_route(inp.topk_ids, sh.E)
+    mixed = np.zeros((sh.T, sh.Kl))
+    for p in range(sh.T * sh.topk):
+        mixed[tok[p]] += float(inp.gate[tok[p], slot[p]]) * H[p]
+    want = mixed[: sh.tokens_per_rank] @ wl.bf16_bits_to_f32(same[0]).astype(np.float64)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    # (2) linear in the gate, and the peers' slices enter once each
+    g2 = (inp.gate * np.float32(4.0)).astype(np.float32)        # a power of two: exact in float
+    a = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, zero, sh.W, 0)
+    b = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, g2, zero, sh.W, 0)
+    assert np.allclose(b, 4.0 * a, rtol=1e-12, atol=1e-12)
+    c = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, inp.peer_slots, sh.W, 0)
+    assert np.allclose(c - a, inp.peer_slots[1].astype(np.float64), rtol=0, atol=1e-9)
+    # (3) gate 1 on slot 0 and 0 on slot 1, integer data: R is row pos(t, 0) of the grouped GEMM, exactly
+    g01 = np.zeros_like(inp.gate); g01[:, 0] = 1.0
+    d = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, g01, zero, sh.W, 0)
+    pos0 = {int(tok[p]): p for p in range(sh.T * sh.topk) if slot[p] == 0}
+    for t in range(sh.tokens_per_rank):
+        e = int(inp.topk_ids[t, 0])
+        row = H[pos0[t]].astype(np.int64) @ wl.bf16_bits_to_f32(inp.W2_ekn[e]).astype(np.int64)
+        assert np.array_equal(d[t], row.astype(np.float64))
+    # (4) argument checks
+    with pytest.raises(Exception):
+        oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, zero, 4, 0)          # T not a multiple of W

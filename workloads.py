@@ -255,3 +255,72 @@ def make_moe(shape: MoeShape, x_dist=None, w_dist=None) -> MoeInputs:
     keys = rng.random((shape.T, shape.E), dtype=np.float32)
     ids = np.argsort(keys, axis=1, kind="stable")[:, : shape.topk].astype(np.int32)
     return MoeInputs(shape, shards, Wt, np.ascontiguousarray(ids))
+
+
+# ----------------------------------------------------------------------------
+# MoE + ReduceScatter (second MoE layer, tensor parallel over K)
+# ----------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class MoeRsShape:
+    """T = W * tokens_per_rank tokens, each routed to `topk` distinct experts; rows of H are the (token, slot) pairs in
+    routing order; per-expert GEMM [rows_e, Kl] x [Kl, N] (this rank's K slice), top-k weighted sum per token, then the
+    sum over ranks of this rank's token slice."""
+    name: str
+    cfg: int
+    W: int
+    tokens_per_rank: int
+    Kl: int             # in hidden / W
+    N: int              # out hidden
+    E: int
+    topk: int
+    h_dist: tuple = ("uniform", 1.0)
+    w_dist: tuple = ("normal", 0.02)
+    slot_dist: tuple = ("normal", 0.2)
+
+    @property
+    def T(self) -> int:
+        return self.W * self.tokens_per_rank
+
+    @property
+    def flops(self) -> int:
+        return 2 * self.T * self.topk * self.Kl * self.N
+
+
+@dataclass
+class MoeRsInputs:
+    shape: MoeRsShape
+    H: np.ndarray          # [T*topk, Kl] uint16 bf16 bits, rows in routing order
+    W2_ekn: np.ndarray     # [E, Kl, N] uint16 bf16 bits
+    topk_ids: np.ndarray   # [T, topk] int32
+    gate: np.ndarray       # [T, topk] float32, positive, rows sum to 1
+    peer_slots: dict       # w -> [tokens_per_rank, N] float32 for every w != rank
+
+
+# Table 5, "MoE-RS-3": 1024 tokens per rank, in hidden 1536 (192 per rank at W = 8), out hidden 2048, 64 experts, top 2
+MOE_RS_FULL = MoeRsShape("moe_rs_full", 15, 8, 1024, 192, 2048, 64, 2)
+MOE_RS_TINY = MoeRsShape("moe_rs_tiny", 16, 4, 24, 64, 72, 5, 2)
+
+
+def make_moe_rs(shape: MoeRsShape, rank: int = 0, h_dist=None, w_dist=None, slot_dist=None) -> MoeRsInputs:
+    h_dist = h_dist or shape.h_dist
+    w_dist = w_dist or shape.w_dist
+    slot_dist = slot_dist or shape.slot_dist
+    rng = np.random.default_rng(_seed(shape.cfg, 0))
+    H = f32_to_bf16_bits(_draw(rng, (shape.T * shape.topk, shape.Kl), *h_dist))
+    rng = np.random.default_rng(_seed(shape.cfg, 100))
+    W2 = np.empty((shape.E, shape.Kl, shape.N), dtype=np.uint16)
+    for e in range(shape.E):
+        W2[e] = f32_to_bf16_bits(_draw(rng, (shape.Kl, shape.N), *w_dist))
+    rng = np.random.default_rng(_seed(shape.cfg, 300))
+    keys = rng.random((shape.T, shape.E), dtype=np.float32)
+    ids = np.argsort(keys, axis=1, kind="stable")[:, : shape.topk].astype(np.int32)
+    g = rng.random((shape.T, shape.topk), dtype=np.float32) + np.float32(0.1)
+    gate = (g / g.sum(axis=1, keepdims=True)).astype(np.float32)
+    slots = {}
+    for w in range(shape.W):
+        if w == rank:
+            continue
+        rng = np.random.default_rng(_seed(shape.cfg, 200 + w))
+        slots[w] = _draw(rng, (shape.tokens_per_rank, shape.N), *slot_dist)
+    return MoeRsInputs(shape, H, W2, np.ascontiguousarray(ids), gate, slots)
