@@ -393,6 +393,41 @@ def main() -> int:
                       "note": "routing + signal-gated grouped GEMM with the emulated gather beside it, per step"}
         del Xs, Wt, Ym
 
+        # MoE + ReduceScatter at the Table 5 shape "MoE-RS-3": grouped GEMM, top-k reduction, reducer; peers pre-signalled
+        mr = wl.MOE_RS_FULL
+        Pr = mr.T * mr.topk
+        Hh = (torch.rand((Pr, mr.Kl), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
+        W2 = (torch.randn((mr.E, mr.N, mr.Kl), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+        ids2 = torch.rand((mr.T, mr.E), device="cuda", generator=gen).argsort(dim=1)[:, : mr.topk].to(torch.int32).contiguous()
+        g2 = torch.rand((mr.T, mr.topk), device="cuda", generator=gen) + 0.1
+        g2 = (g2 / g2.sum(dim=1, keepdim=True)).contiguous()
+        Yw = torch.empty((Pr, mr.N), device="cuda", dtype=torch.float32)
+        tk2 = torch.empty((Pr,), device="cuda", dtype=torch.int32)
+        sg2 = torch.empty((mr.E + 1,), device="cuda", dtype=torch.int32)
+        pp2 = torch.empty((Pr,), device="cuda", dtype=torch.int32)
+        sl2 = [torch.randn((mr.tokens_per_rank, mr.N), device="cuda", dtype=torch.float32) for _ in range(mr.W)]
+        R2 = torch.empty((mr.tokens_per_rank, mr.N), device="cuda", dtype=torch.float32)
+        qctx = agg.symm_alloc(mr.W, 0, 16, mr.W)
+        qp, qc = qctx.streams()
+
+        def step_moe_rs():
+            agg.signal_reset(qctx)
+            for w in range(1, mr.W):
+                agg.signal_set(qctx, w, qc)
+            agg.moe_rs(qctx, mr.T, mr.topk, mr.E, mr.N, mr.Kl, Hh, W2, ids2, g2, Yw, tk2, sg2, pp2, sl2, None, R2, mr.N,
+                       agg.F32, qp, qc)
+
+        t_mrs = timed(step_moe_rs, 20, 3)
+        assert agg.agg_status(qctx) == agg.OK
+        qctx.free()
+        # bytes that have to move: H and the weights once, Y written and read once, the slots read, R written
+        mrs_bytes = (Pr * mr.Kl * 2 + mr.E * mr.N * mr.Kl * 2 + 2 * Pr * mr.N * 4
+                     + (mr.W + 1) * mr.tokens_per_rank * mr.N * 4)
+        out["moe_rs"] = {"workload": mr.name, "ms": round(t_mrs * 1e3, 4), "tflops": round(mr.flops / t_mrs / 1e12, 1),
+                         "algorithmic_GBps": round(mrs_bytes / t_mrs / 1e9, 1),
+                         "note": "routing + grouped GEMM (K = 192 per rank) + top-k reduction + reducer, per step"}
+        del Hh, W2, Yw, sl2
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of rows of the same workload
     if args.cpu_rows > 0:
         import oracle

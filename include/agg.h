@@ -249,6 +249,28 @@ int agg_set_tile_order(agg_ctx* ctx, int order);
 /* Pace of one link of AGG_PRODUCER_LINKS in GB/s (1e9 bytes per second); 0 (default) = as fast as the copy goes. */
 int agg_set_link_rate(agg_ctx* ctx, double gigabytes_per_second);
 
+/* ------------------------------------------------------------------------------------------------
+ * MoE + ReduceScatter for one rank (Section 4.1 "MoE ReduceScatter", Table 5: grouped GEMM, top-k reduction, reduce
+ * scatter; tensor parallel over K).
+ * H: bf16 [Ttok*topk, Klocal], the routed rows in the order of ag_moe_gemm's output (pairs sorted by (expert, token,
+ * slot)); weights2: bf16 [E][N][Klocal]; topk_ids as in ag_moe_gemm; gate: fp32 [Ttok, topk].
+ *   Y[p, :] = H[p, :] . W2_expert(p)                       (Y: caller's fp32 workspace [Ttok*topk, N], overwritten)
+ *   Z[t, :] = sum_s gate[t, s] * Y[pair_pos[t*topk+s], :]  (fp32, slots in order; this rank's tokens go straight into
+ *                                                           slots[rank], the others into row t of Z_other, or nowhere
+ *                                                           if Z_other is NULL)
+ *   R       = sum over w of slots[w]                        (rs_reduce: waits for every slot's signal; this call raises
+ *                                                           the own slot's; the peers' arrive as for gemm_rs)
+ * sorted_token [Ttok*topk], sorted_expert_offsets [E+1], pair_pos [Ttok*topk]: DEVICE int32 outputs the call fills and
+ * uses (pair_pos[t*topk+s] = row of pair (t, s) in the sorted order).  Requirements: Klocal % 64 == 0, N % 4 == 0,
+ * Ttok % W == 0, 16-byte aligned H, weights2, topk_ids, gate, Y, slots, Z_other.  GEMM, top-k reduction and the own
+ * signal run on gemm_stream, the reducer on reduce_stream behind a stream-level wait for that signal.
+ */
+int moe_rs(agg_ctx* ctx, int Ttok, int topk, int E, int N, int Klocal,
+           const void* H, const void* weights2, const int32_t* topk_ids, const float* gate,
+           float* Y, int32_t* sorted_token, int32_t* sorted_expert_offsets, int32_t* pair_pos,
+           const float* const* slots, float* Z_other, void* R, int ldr, int r_dtype,
+           void* gemm_stream, void* reduce_stream);
+
 /* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 128x128.  A tuning knob (Section 3.8); every shape gives the same result up to fp32 summation order. */
 int agg_set_tile_config(agg_ctx* ctx, int tile_config);
 

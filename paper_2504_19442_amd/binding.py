@@ -12,7 +12,7 @@ import os
 
 __all__ = [
     "AggError", "Ctx", "symm_alloc", "signal_reset", "signal_set", "ag_producer_emulate", "ag_gemm",
-    "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "agg_autotune_ag_gemm", "agg_mfma_ceiling", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
+    "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "moe_rs", "agg_autotune_ag_gemm", "agg_mfma_ceiling", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
     "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL", "PRODUCER_LOCAL_LAST",
     "ORDER_ROTATED", "ORDER_SUBCHUNK", "SIGNAL_STRIDE",
     "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM",
@@ -30,7 +30,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT
 EXPORTS = [
     "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
     "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs", "gemm_rs_scatter", "agg_autotune_ag_gemm", "agg_mfma_ceiling",
-    "ag_moe_gemm", "agg_set_tile_config", "agg_set_tile_order", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
+    "ag_moe_gemm", "moe_rs", "agg_set_tile_config", "agg_set_tile_order", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
 ]
 
 
@@ -75,6 +75,7 @@ def _lib() -> C.CDLL:
         L.gemm_rs_scatter.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32, i32, C.POINTER(vp), vp, C.POINTER(vp), i32, vp]
         L.agg_autotune_ag_gemm.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, i32, i32, C.POINTER(vp), i32, i32, vp]
         L.agg_mfma_ceiling.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
+        L.moe_rs.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(vp), vp, vp, i32, i32, vp, vp]
         L.ag_moe_gemm.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32, vp]
         L.agg_strerror.argtypes = [i32]
         L.agg_strerror.restype = C.c_char_p
@@ -248,6 +249,14 @@ def agg_autotune_ag_gemm(ctx: Ctx, M: int, N: int, K: int, B, ldb: int, b_layout
                                        _ptr_array(remote_shards), producer_mode, runs_per_config, C.byref(res)),
            "agg_autotune_ag_gemm")
     return res
+
+
+def moe_rs(ctx: Ctx, Ttok: int, topk: int, E: int, N: int, Klocal: int, H, weights2, topk_ids, gate, Y, sorted_token,
+           sorted_expert_offsets, pair_pos, slots, Z_other, R, ldr: int, r_dtype: int, gemm_stream=None,
+           reduce_stream=None) -> None:
+    _check(_lib().moe_rs(ctx.handle, Ttok, topk, E, N, Klocal, _ptr(H), _ptr(weights2), _ptr(topk_ids), _ptr(gate), _ptr(Y),
+                         _ptr(sorted_token), _ptr(sorted_expert_offsets), _ptr(pair_pos), _ptr_array(slots), _ptr(Z_other),
+                         _ptr(R), ldr, r_dtype, _stream(gemm_stream), _stream(reduce_stream)), "moe_rs")
 
 
 def agg_mfma_ceiling(ctx: Ctx, iterations: int, constant_operands: bool = False, stream=None) -> float:

@@ -64,6 +64,7 @@ struct MoeRouteArgs {
     int P, topk, E;
     int* seg_off;                 // [E + 1] out
     int* sorted_token;            // [P] out
+    int* pair_pos;                // [P] out or nullptr: place of flat pair (token * topk + slot) in the sorted order
     // tile table
     int bm, tiles_n, rows_per_flag, n_flags;
     MoeTile* tile_tab;
@@ -71,6 +72,18 @@ struct MoeRouteArgs {
     int* n_tiles_dev;
 };
 hipError_t launch_moe_route(const MoeRouteArgs& a, hipStream_t stream);
+
+// Top-k reduction of MoE + ReduceScatter: Z[t, :] = sum_s gate[t, s] * Y[pair_pos[t * topk + s], :]
+struct TopkReduceArgs {
+    const float* Y;               // [T * topk, N] fp32, rows in routing order
+    const int* pair_pos;
+    const float* gate;            // [T, topk]
+    int T, topk, N;
+    int own_lo, own_hi;           // tokens of this rank: their rows go to Z_own (row t - own_lo) ...
+    float* Z_own;
+    float* Z_other;               // ... all other tokens to row t of Z_other (nullptr: not computed)
+};
+hipError_t launch_topk_reduce(const TopkReduceArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream_t stream);
 
 enum TileConfig { TILE_256x224 = 0, TILE_128x128 = 1, TILE_CONFIGS };

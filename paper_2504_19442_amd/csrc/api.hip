@@ -656,26 +656,19 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
     return rs_reduce(c, Ms, N, slots, R, ldr, r_dtype, 0, reduce_stream);
 }
 
-int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* weights,
-                int32_t* sorted_token, int32_t* sorted_expert_offsets, void* Y, int ldy, int y_dtype, void* stream)
+// Routing + grouped GEMM, shared by ag_moe_gemm (A = T, rows gathered by token, tiles gated by the signals) and moe_rs
+// (A = the routed rows themselves, nothing to wait for).
+static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* A,
+                        bool gathered, const void* weights, int32_t* sorted_token, int32_t* seg_off, int32_t* pair_pos,
+                        void* Y, int ldy, int y_dtype, hipStream_t stream)
 {
-    if (!c || Ttok < 0 || topk < 1 || E < 1 || E > 4096 || N < 0 || K < 0) return AGG_ERR_INVALID_ARG;
-    if (y_dtype != AGG_BF16 && y_dtype != AGG_F32) return AGG_ERR_INVALID_ARG;
-    if (topk > E) return AGG_ERR_INVALID_ARG;
-    if (Ttok == 0 || N == 0) return AGG_OK;
-    if (!topk_ids || !weights || !sorted_token || !sorted_expert_offsets || !Y) return AGG_ERR_INVALID_ARG;
-    if (K == 0 || K % 64 != 0 || K > (1 << 21)) return AGG_ERR_UNSUPPORTED_SHAPE;
-    if (Ttok % c->W != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
-    const int tpr = Ttok / c->W;                                  // tokens per rank = rows per shard of T
-    if ((size_t)tpr * K * 2 != c->shard_bytes) return AGG_ERR_UNSUPPORTED_SHAPE;
-    const int cps = c->n_signals / c->W;
-    if (tpr % cps != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
     const long long P = (long long)Ttok * topk;
-    const unsigned long long a_bytes = (unsigned long long)Ttok * K * 2;
-    if (P > (1ll << 30) || a_bytes >= (1ull << 31)) return AGG_ERR_UNSUPPORTED_SHAPE;   // 32-bit gather offsets
+    const unsigned long long a_bytes = (unsigned long long)(gathered ? Ttok : P) * K * 2;
+    if (P > (1ll << 30) || a_bytes >= (1ull << 31)) return AGG_ERR_UNSUPPORTED_SHAPE;   // 32-bit row offsets
     if (ldy < N) return AGG_ERR_INVALID_ARG;
-    if (!aligned16(weights) || !aligned16(topk_ids)) return AGG_ERR_MISALIGNED;
+    if (!aligned16(weights) || !aligned16(topk_ids) || !aligned16(A)) return AGG_ERR_MISALIGNED;
     if (reinterpret_cast<uintptr_t>(Y) % (y_dtype == AGG_F32 ? 4 : 2) != 0) return AGG_ERR_MISALIGNED;
+    const int tpr = Ttok / c->W, cps = c->n_signals / c->W;
 
     // Tile shape: segments are ragged (about P / E rows each, a binomial spread around it).  Estimate the tiles
     // each shape would need with segments 15 % above the mean, in waves over the CUs, times the cost of a tile
@@ -723,19 +716,20 @@ int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32
     r.topk = topk;
     r.E = E;
     r.n_tiles_dev = c->moe_ws + 2 * E + 1 + 16;
-    r.seg_off = sorted_expert_offsets;
+    r.seg_off = seg_off;
     r.sorted_token = sorted_token;
+    r.pair_pos = pair_pos;
     r.bm = t.bm;
     r.tiles_n = tiles_n;
-    r.rows_per_flag = tpr / cps;
+    r.rows_per_flag = gathered ? tpr / cps : 1;
     r.n_flags = c->n_signals;
     r.tile_tab = c->moe_tab;
     r.tab_capacity = (int)cap;
-    int rc = hip_fail(launch_moe_route(r, (hipStream_t)stream));
+    int rc = hip_fail(launch_moe_route(r, stream));
     if (rc != AGG_OK) return rc;
 
     GemmParams p{};
-    p.A = (const uint16_t*)c->staging;
+    p.A = (const uint16_t*)A;
     p.B = (const uint16_t*)weights;
     p.C = Y;
     p.lda = K;
@@ -747,19 +741,93 @@ int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32
     p.c_is_f32 = y_dtype == AGG_F32;
     p.c_vec_ok = aligned16(Y) && ((long long)ldy * (p.c_is_f32 ? 4 : 2)) % 16 == 0;
     p.tiles_n = tiles_n;
-    p.flags = c->signals;
+    p.flags = gathered ? c->signals : nullptr;
     p.epoch = c->epoch;
     p.n_flags = c->n_signals;
     p.rows_per_flag = r.rows_per_flag;
     p.wait_ticks = wait_ticks(c);
     p.err = c->err;
-    p.row_index = sorted_token;
+    p.row_index = gathered ? sorted_token : nullptr;      // nullptr: row p of the output reads row p of A
     p.tile_tab = c->moe_tab;
     p.n_tiles_dev = r.n_tiles_dev;
     p.b_group_stride = (long long)N * K;
     p.a_bytes = (unsigned)a_bytes;
     const int grid = (int)(cap < c->num_cus ? cap : c->num_cus);
-    return hip_fail(launch_gemm_grouped(p, cfg, grid, (hipStream_t)stream));
+    return hip_fail(launch_gemm_grouped(p, cfg, grid, stream));
+}
+
+int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* weights,
+                int32_t* sorted_token, int32_t* sorted_expert_offsets, void* Y, int ldy, int y_dtype, void* stream)
+{
+    if (!c || Ttok < 0 || topk < 1 || E < 1 || E > 4096 || N < 0 || K < 0) return AGG_ERR_INVALID_ARG;
+    if (y_dtype != AGG_BF16 && y_dtype != AGG_F32) return AGG_ERR_INVALID_ARG;
+    if (topk > E) return AGG_ERR_INVALID_ARG;
+    if (Ttok == 0 || N == 0) return AGG_OK;
+    if (!topk_ids || !weights || !sorted_token || !sorted_expert_offsets || !Y) return AGG_ERR_INVALID_ARG;
+    if (K == 0 || K % 64 != 0 || K > (1 << 21)) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (Ttok % c->W != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const int tpr = Ttok / c->W;                                  // tokens per rank = rows per shard of T
+    if ((size_t)tpr * K * 2 != c->shard_bytes) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const int cps = c->n_signals / c->W;
+    if (tpr % cps != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    return grouped_gemm(c, Ttok, topk, E, N, K, topk_ids, c->staging, true, weights, sorted_token, sorted_expert_offsets,
+                        nullptr, Y, ldy, y_dtype, (hipStream_t)stream);
+}
+
+int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, const void* weights2,
+           const int32_t* topk_ids, const float* gate, float* Y, int32_t* sorted_token, int32_t* sorted_expert_offsets,
+           int32_t* pair_pos, const float* const* slots, float* Z_other, void* R, int ldr, int r_dtype,
+           void* gemm_stream, void* reduce_stream)
+{
+    if (!c || Ttok < 0 || topk < 1 || topk > 64 || E < 1 || E > 4096 || N < 0 || Kl < 0 || !slots) return AGG_ERR_INVALID_ARG;
+    if (topk > E) return AGG_ERR_INVALID_ARG;
+    if (Ttok % c->W != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (Ttok == 0 || N == 0) return AGG_OK;
+    if (!H || !weights2 || !topk_ids || !gate || !Y || !sorted_token || !sorted_expert_offsets || !pair_pos)
+        return AGG_ERR_INVALID_ARG;
+    if (Kl == 0 || Kl % 64 != 0 || Kl > (1 << 21) || N % 4 != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+    const int W = c->W, Tr = Ttok / W;
+    // the reduction's arguments, checked before anything is enqueued
+    if (!R || ldr < N || (r_dtype != AGG_BF16 && r_dtype != AGG_F32)) return AGG_ERR_INVALID_ARG;
+    if (ldr != N && ldr % 4 != 0) return AGG_ERR_MISALIGNED;
+    for (int w = 0; w < W; ++w)
+        if (!slots[w] || !aligned16(slots[w])) return slots[w] ? AGG_ERR_MISALIGNED : AGG_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(R) % (4 * (r_dtype == AGG_F32 ? 4 : 2)) != 0) return AGG_ERR_MISALIGNED;
+    if (!aligned16(Y) || !aligned16(gate) || (Z_other && !aligned16(Z_other))) return AGG_ERR_MISALIGNED;
+
+    // 1. grouped GEMM on the routed rows (fp32 out)
+    int rc = grouped_gemm(c, Ttok, topk, E, N, Kl, topk_ids, H, false, weights2, sorted_token, sorted_expert_offsets,
+                          pair_pos, Y, N, AGG_F32, (hipStream_t)gemm_stream);
+    if (rc != AGG_OK) return rc;
+    // 2. top-k reduction: this rank's tokens into its own slot (first), the others' into Z_other
+    TopkReduceArgs t{};
+    t.Y = Y;
+    t.pair_pos = pair_pos;
+    t.gate = gate;
+    t.T = Ttok;
+    t.topk = topk;
+    t.N = N;
+    t.own_lo = c->rank * Tr;
+    t.own_hi = t.own_lo + Tr;
+    t.Z_own = const_cast<float*>(slots[c->rank]);
+    t.Z_other = Z_other;
+    if ((rc = hip_fail(launch_topk_reduce(t, c->num_cus * 4, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
+    // 3. notify: the own slot is complete; then the reducer, which waits for the peers' signals itself
+    int32_t* own_flag = c->signals + (size_t)c->rank * (c->n_signals / W) * kSignalStride;
+    if ((rc = hip_fail(launch_signal_set(own_flag, c->epoch, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
+    if (gemm_stream != reduce_stream) {
+        bool waited = false;
+        if (c->can_wait_value) {
+            waited = hipStreamWaitValue32((hipStream_t)reduce_stream, own_flag, (uint32_t)c->epoch, hipStreamWaitValueGte,
+                                          0xFFFFFFFFu) == hipSuccess;
+            if (!waited) (void)hipGetLastError();
+        }
+        if (!waited) {
+            if ((rc = hip_fail(hipEventRecord(c->gemm_done, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
+            if ((rc = hip_fail(hipStreamWaitEvent((hipStream_t)reduce_stream, c->gemm_done, 0))) != AGG_OK) return rc;
+        }
+    }
+    return rs_reduce(c, Tr, N, slots, R, ldr, r_dtype, 0, reduce_stream);
 }
 
 int agg_mfma_ceiling(agg_ctx* c, int iterations, int constant_operands, double* flop, void* stream)

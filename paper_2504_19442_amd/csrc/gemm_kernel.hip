@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gem
                     // gathered row: the token of output row m0 + r; rows past the segment end get an offset outside
                     // the descriptor and load as zero
                     const int row = m0 + u * UNIT_ROWS + ld_row;
-                    const int tok = row < m_lim ? p.row_index[row] : -1;
+                    const int tok = row < m_lim ? (p.row_index ? p.row_index[row] : row) : -1;
                     ld_off[i] = tok >= 0 ? (unsigned)tok * (unsigned)(p.lda * 2) + (unsigned)(chunk * 16) : 0xFFFFFF00u;
                 } else {
                     ld_off[i] = (unsigned)((u * UNIT_ROWS + ld_row) * (int)p.lda * 2 + chunk * 16);

@@ -94,7 +94,10 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
         int pos = running + before + incl - mine;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (v[k] == e) a.sorted_token[pos++] = (i0 + k) / a.topk;
+            if (v[k] == e) {
+                if (a.pair_pos) a.pair_pos[i0 + k] = pos;
+                a.sorted_token[pos++] = (i0 + k) / a.topk;
+            }
         running += total;
         // wave_cnt is used round-robin over four steps, so one barrier per step is enough
     }
@@ -117,6 +120,42 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
         t.pad0 = t.pad1 = 0;
         a.tile_tab[first + k] = t;
     }
+}
+
+// Top-k reduction (Section 4.1, "MoE ReduceScatter", the step between the grouped GEMM and the reduce scatter):
+// every token's `topk` rows of Y are weighted with its gate values and summed in slot order, fp32, starting from the
+// first product.  Streaming: one float4 per lane, tokens of this rank first (their slice is what the reducer waits for).
+__global__ __launch_bounds__(256) void topk_reduce_kernel(const TopkReduceArgs a)
+{
+    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+    const int n4 = a.N / 4;
+    const long long total = (long long)a.T * n4;
+    const int own_n = a.own_hi - a.own_lo;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        int v = (int)(i / n4);                       // place in the order: own tokens first, then the others
+        const int j = (int)(i - (long long)v * n4);
+        int t;
+        if (v < own_n) t = a.own_lo + v;
+        else { t = v - own_n; if (t >= a.own_lo) t += own_n; }
+        const bool own = t >= a.own_lo && t < a.own_hi;
+        if (!own && !a.Z_other) continue;
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < a.topk; ++s) {
+            const int p = a.pair_pos[t * a.topk + s];
+            const float g = a.gate[t * a.topk + s];
+            const f32x4 y = __builtin_nontemporal_load((const f32x4*)(a.Y + (long long)p * a.N) + j);
+            if (s == 0) z = g * y;
+            else z = z + g * y;
+        }
+        f32x4* dst = own ? (f32x4*)(a.Z_own + (long long)(t - a.own_lo) * a.N) + j : (f32x4*)(a.Z_other + (long long)t * a.N) + j;
+        *dst = z;
+    }
+}
+
+hipError_t launch_topk_reduce(const TopkReduceArgs& a, int n_workgroups, hipStream_t stream)
+{
+    hipLaunchKernelGGL(topk_reduce_kernel, dim3(n_workgroups), dim3(256), 0, stream, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_moe_route(const MoeRouteArgs& a, hipStream_t stream)
