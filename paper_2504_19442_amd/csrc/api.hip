@@ -306,6 +306,13 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     a.counters = c->counters;
     a.epoch = c->epoch;
     hipStream_t st = (hipStream_t)producer_stream;
+    // a workgroup addresses its part of a chunk with 32-bit offsets
+    if (mode != AGG_PRODUCER_SDMA) {
+        const int nwg_ = n_workgroups > 0 ? n_workgroups : (c->producer_wgs > 0 ? c->producer_wgs : c->num_cus);
+        const long long sharers = mode == AGG_PRODUCER_LINKS ? (nwg_ / (a.n_jobs > 0 ? a.n_jobs : 1) > 0 ? nwg_ / a.n_jobs : 1)
+                                                             : (a.chunk_bytes / 65536 < nwg_ ? (a.chunk_bytes / 65536 > 0 ? a.chunk_bytes / 65536 : 1) : nwg_);
+        if (a.chunk_bytes / sharers >= (1ll << 31) - 65536) return AGG_ERR_UNSUPPORTED_SHAPE;
+    }
     if (mode == AGG_PRODUCER_KERNEL) {
         const int nwg = n_workgroups > 0 ? n_workgroups : (c->producer_wgs > 0 ? c->producer_wgs : c->num_cus);
         return hip_fail(launch_producer(a, nwg, st));

@@ -93,11 +93,14 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
         }
         int pos = running + before + incl - mine;
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+        for (int k = 0; k < 4; ++k) {
             if (v[k] == e) {
                 if (a.pair_pos) a.pair_pos[i0 + k] = pos;
                 a.sorted_token[pos++] = (i0 + k) / a.topk;
+            } else if (e == 0 && a.pair_pos && i0 + k < a.P && (unsigned)v[k] >= (unsigned)a.E) {
+                a.pair_pos[i0 + k] = -1;          // an id outside [0, E): the pair is nowhere in the sorted order
             }
+        }
         running += total;
         // wave_cnt is used round-robin over four steps, so one barrier per step is enough
     }
@@ -142,10 +145,10 @@ __global__ __launch_bounds__(256) void topk_reduce_kernel(const TopkReduceArgs a
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
         for (int s = 0; s < a.topk; ++s) {
             const int p = a.pair_pos[t * a.topk + s];
+            if (p < 0) continue;                  // a pair with an invalid expert id contributes nothing
             const float g = a.gate[t * a.topk + s];
             const f32x4 y = __builtin_nontemporal_load((const f32x4*)(a.Y + (long long)p * a.N) + j);
-            if (s == 0) z = g * y;
-            else z = z + g * y;
+            z = z + g * y;
         }
         f32x4* dst = own ? (f32x4*)(a.Z_own + (long long)(t - a.own_lo) * a.N) + j : (f32x4*)(a.Z_other + (long long)t * a.N) + j;
         *dst = z;

@@ -166,3 +166,27 @@ def test_moe_rs_full_size_sampled_tokens():
         assert torch.equal(R, R2)
     finally:
         run.close()
+
+
+def test_moe_rs_pair_with_an_invalid_expert_id_contributes_nothing():
+    sh = wl.MOE_RS_TINY
+    inp = wl.make_moe_rs(sh, rank=0)
+    t_bad, s_bad = 7, 1
+    # the oracle's view: the same routing, but that pair's gate is zero
+    gate0 = inp.gate.copy(); gate0[t_bad, s_bad] = 0.0
+    want = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, gate0, inp.peer_slots, sh.W, 0)
+    # the GPU's view: the id itself is invalid, so the pair drops out of the sorted order; H keeps one row per valid
+    # pair in that (shorter) order
+    tok, slot, seg = oracle.moe_route(inp.topk_ids, sh.E)
+    keep = [p for p in range(sh.T * sh.topk) if not (tok[p] == t_bad and slot[p] == s_bad)]
+    H2 = np.zeros_like(inp.H); H2[: len(keep)] = inp.H[keep]
+    ids2 = inp.topk_ids.copy(); ids2[t_bad, s_bad] = 1000
+    bad = wl.MoeRsInputs(sh, H2, inp.W2_ekn, ids2, inp.gate, inp.peer_slots)
+    run = MoeRsRun(bad, 0)
+    try:
+        R, _ = run.run(True, with_other=False)
+        _close(R.cpu().numpy().astype(np.float64), want, sh.Kl)
+        assert run.pos.cpu().numpy().reshape(sh.T, sh.topk)[t_bad, s_bad] == -1
+        assert run.seg.cpu().numpy()[-1] == sh.T * sh.topk - 1
+    finally:
+        run.close()
