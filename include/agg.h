@@ -42,8 +42,10 @@ enum {
 };
 
 enum { AGG_BF16 = 0, AGG_F32 = 1 };          /* element type of an output matrix */
-enum { AGG_B_NK = 0,                         /* B stored [N][K], K contiguous (weight layout of a linear layer) */
-       AGG_B_KN = 1 };                       /* B stored [K][N], N contiguous */
+enum { AGG_B_NK = 0,                         /* B stored [N][K], K contiguous (weight layout of a linear layer): read in place */
+       AGG_B_KN = 1 };                       /* B stored [K][N], N contiguous: transposed into a buffer of the context
+                                                on the GEMM's stream before every GEMM (one more pass over B; the
+                                                first such call allocates the buffer and synchronises); ldb >= N */
 enum { AGG_PRODUCER_KERNEL = 0,              /* copy kernel on a few CUs, release-stores the signals */
        AGG_PRODUCER_SDMA = 1,               /* copy engine (no compute units) + one 4-byte copy per signal */
        AGG_PRODUCER_LINKS = 2,              /* full mesh: every peer's shard on a "link" of its own, all at once, chunk by chunk */
@@ -132,7 +134,7 @@ int ag_producer_emulate(agg_ctx* ctx, const void* const* remote_shards, const in
  * dimension ldb (elements), C row-major with leading dimension ldc (elements) of type c_dtype.
  * Accumulation is fp32; bf16 output is rounded to nearest even from the fp32 accumulator.
  * Each tile waits (acquire) for every signal covering its rows to reach the current epoch before its
- * first load of A.  Requirements: K % 64 == 0, M % W == 0, ldb % 8 == 0, B 16-byte aligned,
+ * first load of A.  Requirements: K % 64 == 0, M % W == 0; for AGG_B_NK ldb % 8 == 0 and B 16-byte aligned;
  * C aligned to its element size; M, N arbitrary (>= 0; 0 is a no-op).
  */
 int ag_gemm(agg_ctx* ctx, int M, int N, int K,

@@ -119,6 +119,7 @@ hipError_t launch_producer_links(const ProducerArgs& a, int n_workgroups, hipStr
 hipError_t launch_signal_set(int* flag, int value, hipStream_t stream);
 hipError_t launch_signal_probe(const int* flag, int value, long long ticks, int* seen, hipStream_t stream);
 
+hipError_t launch_transpose_kn(const uint16_t* B_kn, long long ldb, int K, int N, uint16_t* B_nk, hipStream_t stream);
 hipError_t launch_mfma_ceiling(float* sink, int grid, int iters, int constant_operands, hipStream_t stream);
 
 struct ReduceArgs {
@@ -165,6 +166,8 @@ struct agg_ctx {
     int moe_ws_ints;
     agg::MoeTile* moe_tab;
     int moe_tab_cap;
+    uint16_t* b_nk;       // [N][K] copy of a B that was given as [K][N] (grown on demand)
+    size_t b_nk_elems;
     int can_wait_value;  // the device supports stream waits on a memory word
     hipEvent_t gemm_done; // GEMM-RS: orders the reducer after the GEMM where it does not
 };

@@ -74,11 +74,37 @@ int check_gemm_operands(int M, int N, int K, const void* B, int ldb, int b_layou
     if (b_layout != AGG_B_NK && b_layout != AGG_B_KN) return AGG_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return AGG_OK;
     if (!B || !C) return AGG_ERR_INVALID_ARG;
-    if (b_layout != AGG_B_NK) return AGG_ERR_UNSUPPORTED_SHAPE;
     if (K == 0 || K % 64 != 0 || K > (1 << 21)) return AGG_ERR_UNSUPPORTED_SHAPE;
-    if (ldb < K || ldc < N) return AGG_ERR_INVALID_ARG;
-    if (ldb % 8 != 0 || !aligned16(B)) return AGG_ERR_MISALIGNED;
+    if (ldb < (b_layout == AGG_B_NK ? K : N) || ldc < N) return AGG_ERR_INVALID_ARG;
+    if (b_layout == AGG_B_NK && (ldb % 8 != 0 || !aligned16(B))) return AGG_ERR_MISALIGNED;
+    if (b_layout == AGG_B_KN && reinterpret_cast<uintptr_t>(B) % 2 != 0) return AGG_ERR_MISALIGNED;
     if (reinterpret_cast<uintptr_t>(C) % (c_dtype == AGG_F32 ? 4 : 2) != 0) return AGG_ERR_MISALIGNED;
+    return AGG_OK;
+}
+
+// The GEMM kernel reads B as [N][K].  A B given as [K][N] is transposed first, on the GEMM's stream, into a buffer
+// of the context (grown on demand: the first such call allocates and synchronises).  Callers whose weights do not
+// change should store them as [N][K] and save the pass (2 x N x K x 2 bytes of traffic per call).
+int resolve_b(agg_ctx* c, const void* B, int ldb, int b_layout, int N, int K, hipStream_t stream, const uint16_t** B_nk,
+              long long* ld_nk)
+{
+    if (b_layout == AGG_B_NK) {
+        *B_nk = (const uint16_t*)B;
+        *ld_nk = ldb;
+        return AGG_OK;
+    }
+    const size_t need = (size_t)N * K;
+    if (c->b_nk_elems < need) {
+        HIP_TRY(hipDeviceSynchronize());
+        if (c->b_nk) (void)hipFree(c->b_nk);
+        c->b_nk = nullptr;
+        c->b_nk_elems = 0;
+        HIP_TRY(hipMalloc((void**)&c->b_nk, need * sizeof(uint16_t)));
+        c->b_nk_elems = need;
+    }
+    HIP_TRY(launch_transpose_kn((const uint16_t*)B, ldb, K, N, c->b_nk, stream));
+    *B_nk = c->b_nk;
+    *ld_nk = K;
     return AGG_OK;
 }
 
@@ -178,6 +204,7 @@ int symm_free(agg_ctx* c)
     if (c->producer_stream) (void)hipStreamDestroy(c->producer_stream);
     if (c->consumer_stream) (void)hipStreamDestroy(c->consumer_stream);
     if (c->gemm_done) (void)hipEventDestroy(c->gemm_done);
+    if (c->b_nk) (void)hipFree(c->b_nk);
     if (c->moe_ws) (void)hipFree(c->moe_ws);
     if (c->moe_tab) (void)hipFree(c->moe_tab);
     if (c->staging) (void)hipFree(c->staging);
@@ -377,10 +404,9 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     p.A_local = (const uint16_t*)c->local_shard;
     p.local_lo = c->rank * Ms;
     p.local_hi = p.local_lo + Ms;
-    p.B = (const uint16_t*)B;
+    if ((rc = resolve_b(c, B, ldb, b_layout, N, K, (hipStream_t)consumer_stream, &p.B, &p.ldb)) != AGG_OK) return rc;
     p.C = C;
     p.lda = K;
-    p.ldb = ldb;
     p.ldc = ldc;
     p.M = M;
     p.N = N;
@@ -556,10 +582,9 @@ int gemm_rs_scatter(agg_ctx* c, int M, int N, int Kl, const void* A_local, int l
 
     GemmParams p{};
     p.A = (const uint16_t*)A_local;
-    p.B = (const uint16_t*)B_local;
+    if ((rc = resolve_b(c, B_local, ldb, b_layout, N, Kl, (hipStream_t)gemm_stream, &p.B, &p.ldb)) != AGG_OK) return rc;
     p.C = P_other;
     p.lda = lda;
-    p.ldb = ldb;
     p.ldc = N;
     p.M = M;
     p.N = N;
@@ -618,10 +643,9 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
         if (lda % 8 != 0 || !aligned16(A_local)) return AGG_ERR_MISALIGNED;
         GemmParams p{};
         p.A = (const uint16_t*)A_local + (long long)c->rank * Ms * lda;
-        p.B = (const uint16_t*)B_local;
+        if ((rc = resolve_b(c, B_local, ldb, b_layout, N, Kl, (hipStream_t)gemm_stream, &p.B, &p.ldb)) != AGG_OK) return rc;
         p.C = (void*)slots[c->rank];
         p.lda = lda;
-        p.ldb = ldb;
         p.ldc = N;
         p.M = Ms;
         p.N = N;

@@ -409,3 +409,29 @@ def test_short_and_odd_k_ranges(K):
             assert np.array_equal(C.astype(np.float64), want), (K, tile)      # integer inputs: exact
     finally:
         run.close()
+
+
+def test_b_given_as_k_by_n_is_transposed_first_same_bits():
+    inp = wl.make_ag_gemm(wl.AG_RAGGED)
+    sh = wl.AG_RAGGED
+    run = AgGemmRun(inp, 2)
+    try:
+        base = run.run(tile=1).cpu().numpy()
+        from gpu_util import dev_bf16
+        for pad in (0, 3):                                   # ldb = N and ldb = N + 3 (no alignment asked of this layout)
+            host = np.zeros((sh.K, sh.N + pad), dtype=np.uint16)
+            host[:, : sh.N] = inp.B_kn
+            B_kn = dev_bf16(host)
+            run.poison()
+            agg.signal_reset(run.ctx)
+            C = torch.full((sh.M, sh.N), float("nan"), device="cuda", dtype=torch.float32)
+            torch.cuda.synchronize()
+            agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, B_kn, sh.N + pad, agg.B_KN, C, sh.N, agg.F32, run.cons)
+            agg.ag_producer_emulate(run.ctx, run.remote, None, agg.PRODUCER_KERNEL, 0, run.prod)
+            torch.cuda.synchronize()
+            assert agg.agg_status(run.ctx) == agg.OK
+            assert np.array_equal(C.cpu().numpy().view(np.uint32), base.view(np.uint32))
+        with pytest.raises(agg.AggError):
+            agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, B_kn, sh.N - 1, agg.B_KN, C, sh.N, agg.F32, run.cons)    # ldb < N
+    finally:
+        run.close()
