@@ -36,11 +36,11 @@ inline long long wait_ticks(const agg_ctx* c)
 int choose_tile(const agg_ctx* c, int M, int N)
 {
     if (c->tile_config >= 0) return c->tile_config;
-    const int cand[2] = {TILE_256x224, TILE_128x128};
-    const double eff[2] = {1.0, 0.75};
+    const int cand[3] = {TILE_256x224, TILE_256x256, TILE_128x128};
+    const double eff[3] = {1.0, 1.0, 0.75};
     int best = cand[0];
     double best_cost = 1e300;
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 3; ++i) {
         const TileShape t = tile_shape(cand[i]);
         const long long tiles = (long long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
         const long long waves = (tiles + c->num_cus - 1) / c->num_cus;
@@ -487,7 +487,7 @@ int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb
 {
     if (!c || !out || runs_per_config < 1 || runs_per_config > 1000) return AGG_ERR_INVALID_ARG;
     const int saved_tile = c->tile_config, saved_order = c->tile_order, saved_wgs = c->producer_wgs;
-    const int tiles[2] = {TILE_256x224, TILE_128x128};
+    const int tiles[3] = {TILE_256x224, TILE_256x256, TILE_128x128};
     const int orders[2] = {AGG_ORDER_ROTATED, AGG_ORDER_SUBCHUNK};
     const int wgs[3] = {c->num_cus / 2 > 0 ? c->num_cus / 2 : 1, c->num_cus, 2 * c->num_cus};
     hipEvent_t e0 = nullptr, e1 = nullptr, join = nullptr;
@@ -500,7 +500,7 @@ int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb
         (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return rc;
     }
     const bool sdma = (producer_mode & 0xff) == AGG_PRODUCER_SDMA;
-    for (int ti = 0; ti < 2 && rc == AGG_OK; ++ti)
+    for (int ti = 0; ti < 3 && rc == AGG_OK; ++ti)
         for (int oi = 0; oi < 2 && rc == AGG_OK; ++oi)
             for (int wi = 0; wi < (sdma ? 1 : 3) && rc == AGG_OK; ++wi) {
                 c->tile_config = tiles[ti];
@@ -706,11 +706,11 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     // (the small tile is bound by the global->LDS path: about 0.6 of the large tile's rate per flop).
     int cfg = c->tile_config;
     if (cfg < 0) {
-        const int cand[2] = {TILE_256x224, TILE_128x128};
-        const double eff[2] = {1.0, 0.6};
+        const int cand[3] = {TILE_256x224, TILE_256x256, TILE_128x128};
+        const double eff[3] = {1.0, 1.0, 0.6};
         const double rows = 1.15 * (double)P / E;
         double best = 1e300;
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 3; ++i) {
             const TileShape ts = tile_shape(cand[i]);
             const long long mt = (long long)((rows + ts.bm - 1) / ts.bm);
             const long long tiles = (long long)E * mt * ((N + ts.bn - 1) / ts.bn);

@@ -110,7 +110,7 @@ struct Cfg {
 #ifndef AGG_RING_BIG
 #define AGG_RING_BIG 35
 #endif
-    static constexpr int RW = (BM == 256) ? AGG_RING_BIG : 32;
+    static constexpr int RW = (BM == 256 && BN == 256) ? 36 : (BM == 256) ? AGG_RING_BIG : 32;
     static constexpr int RING_BYTES = RW * 4096;
     static constexpr int PERIOD = std::lcm(L, RW) / L;     // stages after which ring positions repeat
     // epilogue staging: each wave stages 32 rows x BN columns at a time
@@ -120,7 +120,7 @@ struct Cfg {
     static_assert(BM % 128 == 0 && BN % 32 == 0, "tile shape");
     static_assert(A_UNITS % 4 == 0 && B_UNITS % 4 == 0, "units must split evenly over 4 waves");
     static_assert(RW >= 2 * L && RW <= 63, "ring: at least two stages, and the prologue's loads fit the vmcnt range");
-    static_assert(PERIOD <= 8, "the main loop is unrolled over PERIOD stages");
+    static_assert(PERIOD <= 9, "the main loop is unrolled over PERIOD stages");
     static_assert(ACC == 64 || ACC == 128 || ACC == 224 || ACC == 256, "add a reservation line for this accumulator count");
     // One quarter-step is SLOTS = MB*NB MFMAs.  Its memory instructions, in order: LQ global->LDS loads
     // (while a stage's loads are being issued: the three quarter-steps after a barrier), then the F = MB+NB
@@ -139,7 +139,7 @@ struct Cfg {
 // through row_index, B is the tile's expert's matrix, and rows at or past the tile's segment end are neither loaded
 // (they read as zero) nor stored.
 template <int BM, int BN, bool GROUPED>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(224))) void gemm_kernel(const GemmParams p)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gemm_kernel(const GemmParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)    // the body names gfx950 registers; the host pass only needs the launch stub
     using C_ = Cfg<BM, BN>;
@@ -631,6 +631,7 @@ hipError_t launch_gemm(const GemmParams& p, int cfg, int grid, hipStream_t strea
 {
     switch (cfg) {
         case TILE_256x224: return launch_cfg<256, 224, false>(p, grid, stream);
+        case TILE_256x256: return launch_cfg<256, 256, false>(p, grid, stream);
         default: return launch_cfg<128, 128, false>(p, grid, stream);
     }
 }
@@ -639,6 +640,7 @@ hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream
 {
     switch (cfg) {
         case TILE_256x224: return launch_cfg<256, 224, true>(p, grid, stream);
+        case TILE_256x256: return launch_cfg<256, 256, true>(p, grid, stream);
         default: return launch_cfg<128, 128, true>(p, grid, stream);
     }
 }

@@ -62,7 +62,7 @@ def test_tiny_bit_identical_over_all_arrival_orders_and_launch_orders():
         run.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1])
+@pytest.mark.parametrize("tile", [0, 1, 2])
 def test_integer_inputs_are_exact(tile):
     # entries in {-2..2}: every partial sum is an integer below 2^24, so fp32 accumulation is exact
     inp = wl.make_ag_gemm(wl.AG_RAGGED, a_dist=("int", 2), b_dist=("int", 2))
@@ -87,7 +87,7 @@ def test_identity_b_returns_gathered_a_bit_exactly():
         run.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1])
+@pytest.mark.parametrize("tile", [0, 1, 2])
 @pytest.mark.parametrize("chunks", [1, 4])
 def test_ragged_shape_f32_and_bf16(tile, chunks):
     inp = wl.make_ag_gemm(wl.AG_RAGGED)         # M=600, N=328, K=320: ragged against every tile shape
@@ -333,7 +333,7 @@ def test_world_of_one_is_a_plain_gemm():
     assert np.array_equal(want, oracle.ag_gemm(inp.shards, inp.B_kn, 0))
     run = AgGemmRun(inp, 0)
     try:
-        for tile in (0, 1):
+        for tile in (0, 1, 2):
             check_f32(run.run(tile=tile).cpu().numpy(), want, sh.K)
     finally:
         run.close()
@@ -381,14 +381,14 @@ def test_autotuner_runs_the_whole_function_and_leaves_a_working_configuration():
         e_before = run.ctx.epoch
         res = agg.agg_autotune_ag_gemm(run.ctx, sh.M, sh.N, sh.K, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.remote,
                                        agg.PRODUCER_KERNEL, 2)
-        assert res.configs_tried == 12 and res.tile_config in (0, 1) and res.tile_order in (0, 1)
+        assert res.configs_tried == 18 and res.tile_config in (0, 1, 2) and res.tile_order in (0, 1)
         assert res.producer_workgroups > 0 and 0.0 < res.best_ms < 1000.0
-        assert run.ctx.epoch == e_before + 12 * 3 + 29     # the signals were reset before every single run
+        assert run.ctx.epoch == e_before + 18 * 3 + 29     # the signals were reset before every single run
         check_f32(C.cpu().numpy(), want, sh.K)              # the last tuning run left a complete, correct C
         check_f32(run.run().cpu().numpy(), want, sh.K)      # and the chosen configuration works
         res2 = agg.agg_autotune_ag_gemm(run.ctx, sh.M, sh.N, sh.K, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.remote,
                                         agg.PRODUCER_SDMA, 1)
-        assert res2.configs_tried == 4 and res2.producer_workgroups == 0
+        assert res2.configs_tried == 6 and res2.producer_workgroups == 0
         with pytest.raises(agg.AggError):
             agg.agg_autotune_ag_gemm(run.ctx, sh.M, sh.N, sh.K + 8, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.remote,
                                      agg.PRODUCER_KERNEL, 1)
@@ -404,7 +404,7 @@ def test_short_and_odd_k_ranges(K):
     want = oracle.ag_gemm(inp.shards, inp.B_kn, 1)
     run = AgGemmRun(inp, 1)
     try:
-        for tile in (0, 1):
+        for tile in (0, 1, 2):
             C = run.run(tile=tile).cpu().numpy()
             assert np.array_equal(C.astype(np.float64), want), (K, tile)      # integer inputs: exact
     finally:

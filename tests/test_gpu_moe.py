@@ -70,7 +70,7 @@ def _check_y(Y, want, K, scale=1.0):
 
 
 @pytest.mark.parametrize("rank", [0, 2])
-@pytest.mark.parametrize("tile", [0, 1])
+@pytest.mark.parametrize("tile", [0, 1, 2])
 def test_moe_tiny_against_oracle(rank, tile):
     sh = wl.MOE_TINY
     inp = wl.make_moe(sh)
