@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
 hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream)
 {
     switch (a.W) {
-        case 8: hipLaunchKernelGGL((reduce_kernel<8, 1>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
+        case 8: hipLaunchKernelGGL((reduce_kernel<8, 2>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
         case 4: hipLaunchKernelGGL((reduce_kernel<4, 2>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
         case 2: hipLaunchKernelGGL((reduce_kernel<2, 4>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
         default: hipLaunchKernelGGL((reduce_kernel<0, 2>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
