@@ -16,6 +16,8 @@
  *     of T[r * |R| ...], in that order.
  *   - AG+MoE (Section 4.1, Table 4): a grouped GEMM over expert segments of the
  *     gathered tokens.
+ *   - MoE+RS (Section 4.1, Table 5): grouped GEMM on the routed rows, top-k
+ *     weighted reduction per token, sum of the ranks' partial slices.
  * Inputs are bf16 bit patterns; products and sums are taken in fp64 (a bf16 x bf16
  * product is exact in fp64, so only the additions round).  The one fp32 routine
  * (oracle_rs_reduce_f32) exists because the reducer's precision is fixed to fp32
