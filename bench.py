@@ -93,8 +93,9 @@ def main() -> int:
                     help="rate of one emulated link of the full-mesh block (one direction of an xGMI link)")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--pmc-calibration", action="store_true",
-                    help="profiling aid: also run one plain 256 MiB device copy, the known-size kernel that the "
-                         "FETCH_SIZE / WRITE_SIZE counters are scaled by")
+                    help="profiling aid for rocprofv3 --pmc runs: also run one plain 256 MiB device copy, the known-size "
+                         "kernel that the FETCH_SIZE / WRITE_SIZE counters are scaled by, and launch producer and "
+                         "consumer on one stream (counter collection runs kernels one at a time)")
     ap.add_argument("--no-extras", action="store_true", help="skip the reducer / serial / copy-only timings")
     ap.add_argument("--shape", default="", help="profiling aid: W,Ms,K,N of an ad-hoc AllGather-GEMM shape")
     ap.add_argument("--only-gemm", action="store_true",
@@ -133,10 +134,15 @@ def main() -> int:
     hev = HipEvents()
     ev_cons_done = hev.new(timing=False)
 
+    # Counter collection runs one kernel at a time, in the order the queues offer them: a consumer that gets its turn
+    # before its producer would wait for signals that cannot come.  Under --pmc-calibration (the counter runs) the
+    # producer therefore goes on the consumer's stream, ahead of the GEMM; per-kernel counters are not affected.
+    step_prod = cons if args.pmc_calibration else prod
+
     def step_fused(ev_pairs=None):
         agg.signal_reset(ctx)
         hev.wait(prod_h, ev_cons_done)         # T is shared: the next arrival waits for the last consumer
-        agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL | local_flag, args.producer_wgs, prod)
+        agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL | local_flag, args.producer_wgs, step_prod)
         if ev_pairs is not None:
             e0, e1 = ev_pairs[step_fused.k]
             step_fused.k += 1
