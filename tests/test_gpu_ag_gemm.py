@@ -435,3 +435,46 @@ def test_b_given_as_k_by_n_is_transposed_first_same_bits():
             agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, B_kn, sh.N - 1, agg.B_KN, C, sh.N, agg.F32, run.cons)    # ldb < N
     finally:
         run.close()
+
+
+def test_seeded_random_shapes_and_settings_exact():
+    """Thirty seeded combinations of world size, shard rows, K, N, signals per shard, tile shape, tile order, producer,
+    own-shard handling, output type and launch order; integer inputs, so every result must equal the oracle exactly."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 30:
+        W = int(rng.choice([1, 2, 3, 4, 5, 8]))
+        cps = int(rng.choice([1, 2, 4]))
+        Ms = max(int(rng.choice([8, 32, 64, 100, 128, 200, 256, 264, 512])) // cps * cps, cps)
+        K = 64 * int(rng.integers(1, 12))
+        N = int(rng.choice([8, 24, 100, 101, 128, 222, 224, 232, 256, 257, 300, 448, 520, 736]))
+        rank = int(rng.integers(0, W))
+        tile = int(rng.choice([-1, 0, 1, 2]))
+        order = int(rng.choice([agg.ORDER_ROTATED, agg.ORDER_SUBCHUNK]))
+        mode = int(rng.choice([agg.PRODUCER_KERNEL, agg.PRODUCER_LINKS, agg.PRODUCER_SDMA]))
+        local = bool(rng.integers(0, 2))
+        out = int(rng.choice([agg.F32, agg.BF16]))
+        consumer_first = bool(rng.integers(0, 2))
+        if (Ms * K * 2) % (cps * 16) != 0:
+            continue
+        what = (W, rank, Ms, K, N, cps, tile, order, mode, local, out, consumer_first)
+        print("[random case]", what, flush=True)
+        sh = wl.AgGemmShape("ag_random", 50 + done, W, Ms, K, N)
+        inp = wl.make_ag_gemm(sh, a_dist=("int", 2), b_dist=("int", 2))
+        want = oracle.ag_gemm(inp.shards, inp.B_kn, rank)
+        run = AgGemmRun(inp, rank, chunks_per_shard=cps)
+        try:
+            run.ctx.set_tile_order(order)
+            flag = 0
+            if local:
+                run.ctx.set_local_shard(run.remote[rank])
+                flag = agg.PRODUCER_LOCAL_LAST
+            arrival = wl.arrival_orders(W, rank, limit=3, seed=done)[-1] if W > 1 else None
+            C = run.run(arrival, out_dtype=out, mode=mode | flag, tile=tile, consumer_first=consumer_first)
+            if out == agg.F32:
+                assert np.array_equal(C.cpu().numpy().astype(np.float64), want), what
+            else:
+                assert np.array_equal(host_bits(C), wl.f32_to_bf16_bits(want.astype(np.float32))), what
+        finally:
+            run.close()
+        done += 1
