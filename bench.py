@@ -91,7 +91,7 @@ def main() -> int:
                          "with the local copy into T done last)")
     ap.add_argument("--link-gbps", type=float, default=76.8,
                     help="rate of one emulated link of the full-mesh block (one direction of an xGMI link)")
-    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="rows of C the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="profiling aid for rocprofv3 --pmc runs: also run one plain 256 MiB device copy, the known-size "
                          "kernel that the FETCH_SIZE / WRITE_SIZE counters are scaled by, and launch producer and "
