@@ -478,3 +478,35 @@ def test_seeded_random_shapes_and_settings_exact():
         finally:
             run.close()
         done += 1
+
+
+def test_all_ranks_on_one_gpu_assemble_the_full_product():
+    """W emulated ranks, each with its own symmetric buffer, pulling the others' shards and multiplying by its own column
+    slice of B: side by side the W outputs are A . B of the whole problem (Section 2.3: the tensor-parallel AG + GEMM)."""
+    W, Ms, K, Nl = 4, 128, 192, 136
+    rng = np.random.default_rng(77)
+    A = [wl.f32_to_bf16_bits(rng.uniform(-1, 1, (Ms, K)).astype(np.float32)) for _ in range(W)]
+    B = [wl.f32_to_bf16_bits(rng.normal(0, 0.05, (K, Nl)).astype(np.float32)) for _ in range(W)]
+    want = oracle.gemm(np.concatenate(A), np.concatenate(B, axis=1))
+    from gpu_util import dev_bf16
+    L = [dev_bf16(a) for a in A]                                   # rank r's local shard: every rank pulls from these
+    Bd = [dev_bf16(np.ascontiguousarray(b.T)) for b in B]
+    ctxs = [agg.symm_alloc(W, r, Ms * K * 2, 2 * W) for r in range(W)]
+    C = [torch.full((W * Ms, Nl), float("nan"), device="cuda", dtype=torch.float32) for _ in range(W)]
+    try:
+        for r, ctx in enumerate(ctxs):
+            agg.signal_reset(ctx)
+            ps, cs = ctx.streams()
+            # producers first: eight streams share the device's few hardware queues
+            agg.ag_producer_emulate(ctx, L, None, agg.PRODUCER_KERNEL if r % 2 else agg.PRODUCER_LINKS, 0, ps)
+        for r, ctx in enumerate(ctxs):
+            ps, cs = ctx.streams()
+            agg.ag_gemm(ctx, W * Ms, Nl, K, Bd[r], K, agg.B_NK, C[r], Nl, agg.F32, cs)
+        torch.cuda.synchronize()
+        for ctx in ctxs:
+            assert agg.agg_status(ctx) == agg.OK
+        got = torch.cat(C, dim=1).cpu().numpy()
+        check_f32(got, want, K)
+    finally:
+        for ctx in ctxs:
+            ctx.free()
