@@ -360,8 +360,25 @@ def main() -> int:
 
         t_grs = timed(step_gemm_rs, 20, 3)
         assert agg.agg_status(gctx) == agg.OK
+        # the schedule of a node: own slice last, its four row chunks signalled one by one to the reducer
+        gctx.free()
+        gctx = agg.symm_alloc(rs.W, 0, 16, rs.W * 4)
+        gp, gc = gctx.streams()
+        gctx.set_rs_chunks(4)
+        gctx.set_rs_own_slice_last(True)
+
+        def step_gemm_rs_own_last():
+            agg.signal_reset(gctx)
+            for s in range(4, rs.W * 4):
+                agg.signal_set(gctx, s, gc)
+            agg.gemm_rs(gctx, rs.M, rs.N, rs.Kl, A_loc, rs.Kl, B_loc, rs.Kl, agg.B_NK, slots, P_other, R, rs.N,
+                        agg.F32, gp, gc)
+
+        t_grs_last = timed(step_gemm_rs_own_last, 20, 3)
+        assert agg.agg_status(gctx) == agg.OK
         gctx.free()
         out["gemm_rs"] = {"workload": rs.name, "ms": round(t_grs * 1e3, 4),
+                          "ms_own_slice_last_4_chunks": round(t_grs_last * 1e3, 4),
                           "gemm_tflops": round(2.0 * rs.M * rs.N * rs.Kl / t_grs / 1e12, 1),
                           "note": "GEMM (fp32 out, 8192x8192x3584) + reducer on a second stream, per step"}
         del A_loc, B_loc, P_other, slots, R

@@ -248,6 +248,30 @@ int agg_set_local_shard(agg_ctx* ctx, const void* local_shard);
 enum { AGG_ORDER_ROTATED = 0, AGG_ORDER_SUBCHUNK = 1 };
 int agg_set_tile_order(agg_ctx* ctx, int order);
 
+/*
+ * Granularity of the GEMM + ReduceScatter signals (Section 3.6: the scatter is asynchronous and the reduction starts
+ * on what has arrived; Algorithm 3's notify / wait pair, taken per block of rows instead of per whole slice).  With
+ * chunks = k > 1 every slice of M / W rows is cut into k row chunks of M / (W k) rows, each with a signal of its own:
+ *   - gemm_rs_scatter raises slice_signal[w][c * AGG_SIGNAL_STRIDE] when chunk c of slice w is complete at its
+ *     destination (so slice_signal[w] must point at k signal words spaced AGG_SIGNAL_STRIDE apart);
+ *   - rs_reduce (and the reducers inside gemm_rs and moe_rs) waits for signal w * (n_signals / W) + c before its first
+ *     read of chunk c of slot w, and reduces the first chunks while later ones are still being produced.  A workgroup
+ *     waits for a chunk of ALL W slots before it adds that chunk up; the order of the additions is unchanged, so the
+ *     result is the same bit for bit for every k.
+ * Whoever plays the peers sets their k signals per slot.  1 <= k <= 16, k <= n_signals / W; M / W must be a multiple
+ * of k and (M / (W k)) * N a multiple of 4 (else AGG_ERR_UNSUPPORTED_SHAPE from the launch).  Default 1.
+ */
+int agg_set_rs_chunks(agg_ctx* ctx, int chunks);
+
+/*
+ * Order of the slices inside gemm_rs (Section 3.7: a rank computes the slices that have to travel first and keeps its
+ * own for last).  0 (default): the own slice first -- on one GPU the peers' slots are there early, so the reducer can
+ * run beside the whole rest of the GEMM.  1: the own slice last, as on a node; the reducer then starts when the first
+ * chunk of the own slice (agg_set_rs_chunks) is complete and reduces chunk by chunk behind the GEMM.  The results are
+ * the same bit for bit.
+ */
+int agg_set_rs_own_slice_last(agg_ctx* ctx, int on);
+
 /* Pace of one link of AGG_PRODUCER_LINKS in GB/s (1e9 bytes per second); 0 (default) = as fast as the copy goes. */
 int agg_set_link_rate(agg_ctx* ctx, double gigabytes_per_second);
 

@@ -30,7 +30,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT
 EXPORTS = [
     "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
     "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs", "gemm_rs_scatter", "agg_autotune_ag_gemm", "agg_mfma_ceiling",
-    "ag_moe_gemm", "moe_rs", "agg_set_tile_config", "agg_set_tile_order", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
+    "ag_moe_gemm", "moe_rs", "agg_set_tile_config", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
 ]
 
 
@@ -65,6 +65,8 @@ def _lib() -> C.CDLL:
         L.agg_set_wait_limit_us.argtypes = [vp, u64]
         L.agg_set_tile_config.argtypes = [vp, i32]
         L.agg_set_tile_order.argtypes = [vp, i32]
+        L.agg_set_rs_chunks.argtypes = [vp, i32]
+        L.agg_set_rs_own_slice_last.argtypes = [vp, i32]
         L.agg_set_local_shard.argtypes = [vp, vp]
         L.agg_set_link_rate.argtypes = [vp, C.c_double]
         L.agg_status.argtypes = [vp]
@@ -156,6 +158,12 @@ class Ctx:
 
     def set_tile_order(self, order: int) -> None:
         _check(_lib().agg_set_tile_order(self.handle, int(order)), "agg_set_tile_order")
+
+    def set_rs_own_slice_last(self, on: bool) -> None:
+        _check(_lib().agg_set_rs_own_slice_last(self.handle, 1 if on else 0), "agg_set_rs_own_slice_last")
+
+    def set_rs_chunks(self, chunks: int) -> None:
+        _check(_lib().agg_set_rs_chunks(self.handle, int(chunks)), "agg_set_rs_chunks")
 
     def set_local_shard(self, local_shard) -> None:
         _check(_lib().agg_set_local_shard(self.handle, _ptr(local_shard)), "agg_set_local_shard")

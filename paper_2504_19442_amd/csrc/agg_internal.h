@@ -10,6 +10,7 @@ namespace agg {
 
 constexpr int kMaxWorld = 64;          // kernel-argument arrays are sized for this many ranks
 constexpr int kSignalStride = AGG_SIGNAL_STRIDE;
+constexpr int kMaxRsChunks = 16;       // row chunks per GEMM-RS slice (each with its own counter and signal)
 
 // What one GEMM launch needs.  A is row-major [M][K] bf16 (optionally gathered through row_index),
 // B is [N][K] bf16 (K contiguous), C row-major.
@@ -39,8 +40,9 @@ struct GemmParams {
     int* err;             // device word: set to 1 when a wait is given up
     // GEMM-RS scatter (n_slices > 0): the rows are cut into slices of slice_rows; slice w is stored at
     // slice_dst[w] (row index relative to the slice, leading dimension ldc_slice) where that is not null, else in C.
-    // Tiles touching slice w count up slice_ctr[w]; the last one raises slice_flag[w] (where not null).
-    int n_slices, slice_rows;
+    // Each slice is cut further into slice_chunks row chunks of chunk_rows.  Tiles touching chunk c of slice w count
+    // up slice_ctr[w * slice_chunks + c]; the last one raises slice_flag[w][c * kSignalStride] (where not null).
+    int n_slices, slice_rows, slice_chunks, chunk_rows;
     long long ldc_slice;
     int* slice_ctr;
     void* slice_dst[kMaxWorld];
@@ -134,11 +136,13 @@ struct ReduceArgs {
     int N;
     const int* flags;
     int flag_step;                // signal index of slot w = w * flag_step
+    int chunks;                   // > 1: slot w arrives in this many row chunks, chunk c on signal w * flag_step + c
+    long long chunk_vec4;         // float4 elements per chunk
     int epoch;
     long long wait_ticks;
     int* err;
 };
-hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream);
+hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream, bool beside_gemm);
 
 }  // namespace agg
 
@@ -158,6 +162,8 @@ struct agg_ctx {
     int device;
     int tile_config;     // -1 = automatic
     int tile_order;      // AGG_ORDER_*
+    int rs_own_last;     // gemm_rs computes the own slice last (1) or first (0)
+    int rs_chunks;       // row chunks per GEMM-RS slice and reducer slot, each with a signal of its own (>= 1)
     int producer_wgs;    // workgroups of the producer kernel when the caller passes 0 (0 = one per CU)
     const void* local_shard;  // see agg_set_local_shard
     double link_GBps;    // pace of a link of the full-mesh producer (0 = not paced)

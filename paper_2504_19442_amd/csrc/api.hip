@@ -159,11 +159,12 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     c->epoch = 1;
     c->wait_limit_us = 2000000;
     c->tile_config = -1;
+    c->rs_chunks = 1;
     int rc = AGG_OK;
     hipDeviceProp_t prop;
     int khz = 0;
     const size_t sig_bytes = (size_t)n_signals * kSignalStride * sizeof(int);
-    const size_t ctr_bytes = ((size_t)n_signals + kMaxWorld + 32) * sizeof(int);   // producer counters, then one per GEMM-RS slice
+    const size_t ctr_bytes = ((size_t)n_signals + kMaxWorld * kMaxRsChunks + 32) * sizeof(int);   // producer counters, then one per chunk of a GEMM-RS slice
     if ((rc = hip_fail(hipGetDevice(&c->device))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipGetDeviceProperties(&prop, c->device))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device))) != AGG_OK) goto fail;
@@ -262,6 +263,20 @@ int agg_set_tile_order(agg_ctx* c, int order)
 {
     if (!c || (order != AGG_ORDER_ROTATED && order != AGG_ORDER_SUBCHUNK)) return AGG_ERR_INVALID_ARG;
     c->tile_order = order;
+    return AGG_OK;
+}
+
+int agg_set_rs_chunks(agg_ctx* c, int chunks)
+{
+    if (!c || chunks < 1 || chunks > kMaxRsChunks || chunks > c->n_signals / c->W) return AGG_ERR_INVALID_ARG;
+    c->rs_chunks = chunks;
+    return AGG_OK;
+}
+
+int agg_set_rs_own_slice_last(agg_ctx* c, int on)
+{
+    if (!c || (on != 0 && on != 1)) return AGG_ERR_INVALID_ARG;
+    c->rs_own_last = on;
     return AGG_OK;
 }
 
@@ -438,8 +453,8 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     return hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)consumer_stream));
 }
 
-int rs_reduce(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int ldr, int r_dtype, int n_workgroups,
-              void* stream)
+static int reduce_impl(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int ldr, int r_dtype, int n_workgroups,
+                       void* stream, bool beside_gemm)
 {
     if (!c || !slots || Ms < 0 || N < 0 || n_workgroups < 0 || n_workgroups > 65536) return AGG_ERR_INVALID_ARG;
     if (r_dtype != AGG_BF16 && r_dtype != AGG_F32) return AGG_ERR_INVALID_ARG;
@@ -465,6 +480,11 @@ int rs_reduce(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int
     a.N = N;
     a.flags = c->signals;
     a.flag_step = c->n_signals / c->W;
+    a.chunks = c->rs_chunks;
+    if (a.chunks > 1) {
+        if (Ms % a.chunks != 0 || ((long long)(Ms / a.chunks) * N) % 4 != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
+        a.chunk_vec4 = (long long)(Ms / a.chunks) * N / 4;
+    }
     a.epoch = c->epoch;
     a.wait_ticks = wait_ticks(c);
     a.err = c->err;
@@ -476,7 +496,13 @@ int rs_reduce(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int
         nwg = (int)(need < (long long)c->num_cus * 2 ? need : (long long)c->num_cus * 2);
         if (nwg < 1) nwg = 1;
     }
-    return hip_fail(launch_reduce(a, nwg, (hipStream_t)stream));
+    return hip_fail(launch_reduce(a, nwg, (hipStream_t)stream, beside_gemm));
+}
+
+int rs_reduce(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int ldr, int r_dtype, int n_workgroups,
+              void* stream)
+{
+    return reduce_impl(c, Ms, N, slots, R, ldr, r_dtype, n_workgroups, stream, false);
 }
 
 // Tuning in the manner of Section 3.8: the unit that is timed is the whole overlapped function -- reset of the
@@ -567,6 +593,7 @@ int gemm_rs_scatter(agg_ctx* c, int M, int N, int Kl, const void* A_local, int l
     if (first_slice < 0 || first_slice >= c->W) return AGG_ERR_INVALID_ARG;
     const int W = c->W, Ms = M / W;
     if (M == 0 || N == 0) return AGG_OK;
+    if (Ms % c->rs_chunks != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
     // every slice needs somewhere to go
     const void* any_dst = P_other;
     for (int w = 0; w < W; ++w) {
@@ -597,8 +624,10 @@ int gemm_rs_scatter(agg_ctx* c, int M, int N, int Kl, const void* A_local, int l
     p.wait_ticks = wait_ticks(c);
     p.n_slices = W;
     p.slice_rows = Ms;
+    p.slice_chunks = c->rs_chunks;
+    p.chunk_rows = Ms / c->rs_chunks;
     p.ldc_slice = N;
-    p.slice_ctr = c->counters + c->n_signals;          // W counters of their own, after the producer's
+    p.slice_ctr = c->counters + c->n_signals;          // counters of their own, after the producer's
     for (int w = 0; w < W; ++w) {
         p.slice_dst[w] = slice_dst[w];
         p.slice_flag[w] = slice_signal ? slice_signal[w] : nullptr;
@@ -619,6 +648,7 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
     const int W = c->W, Ms = M / W;
     if (M == 0 || N == 0) return AGG_OK;
     if (!slots[c->rank]) return AGG_ERR_INVALID_ARG;
+    if (Ms % c->rs_chunks != 0 || ((long long)(Ms / c->rs_chunks) * N) % 4 != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
     // validate the reduction's arguments before anything is enqueued
     if (!R || ldr < N || (r_dtype != AGG_BF16 && r_dtype != AGG_F32)) return AGG_ERR_INVALID_ARG;
     if (((long long)Ms * N) % 4 != 0 || (ldr != N && N % 4 != 0)) return AGG_ERR_UNSUPPORTED_SHAPE;
@@ -635,7 +665,8 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
         int32_t* sig[kMaxWorld] = {nullptr};
         dst[c->rank] = const_cast<float*>(slots[c->rank]);
         sig[c->rank] = own_flag;
-        rc = gemm_rs_scatter(c, M, N, Kl, A_local, lda, B_local, ldb, b_layout, dst, P_other, sig, c->rank, gemm_stream);
+        const int first = c->rs_own_last ? (c->rank + 1) % W : c->rank;
+        rc = gemm_rs_scatter(c, M, N, Kl, A_local, lda, B_local, ldb, b_layout, dst, P_other, sig, first, gemm_stream);
     } else {
         // only the own slice is wanted: a GEMM over its Ms rows, seen as a world of one slice
         rc = check_gemm_operands(Ms, N, Kl, B_local, ldb, b_layout, slots[c->rank], N, AGG_F32);
@@ -658,6 +689,8 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
         p.wait_ticks = wait_ticks(c);
         p.n_slices = 1;
         p.slice_rows = Ms;
+        p.slice_chunks = c->rs_chunks;
+        p.chunk_rows = Ms / c->rs_chunks;
         p.ldc_slice = N;
         p.slice_ctr = c->counters + c->n_signals;
         p.slice_flag[0] = own_flag;
@@ -673,11 +706,16 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
     // the two would wait for each other; so the reduce stream itself waits (no compute unit is held) until the own
     // slice is signalled, and the reducer then runs beside the rest of the GEMM.  The stream wait ends at the
     // latest when the GEMM kernel has completed, so it needs no time limit of its own.
+    // With the own slice computed last and cut into chunks, the stream waits for its first chunk only: by then every
+    // workgroup of the (persistent) GEMM has long been resident, and the reducer takes the later chunks' signals itself.
     if (gemm_stream != reduce_stream) {
         bool waited = false;
         if (c->can_wait_value) {
-            waited = hipStreamWaitValue32((hipStream_t)reduce_stream, own_flag, (uint32_t)c->epoch, hipStreamWaitValueGte,
-                                          0xFFFFFFFFu) == hipSuccess;
+            const int n_wait = (c->rs_own_last && P_other) ? 1 : c->rs_chunks;
+            waited = true;
+            for (int ch = 0; waited && ch < n_wait; ++ch)
+                waited = hipStreamWaitValue32((hipStream_t)reduce_stream, own_flag + ch * kSignalStride, (uint32_t)c->epoch,
+                                              hipStreamWaitValueGte, 0xFFFFFFFFu) == hipSuccess;
             if (!waited) (void)hipGetLastError();
         }
         if (!waited) {   // no stream wait on memory here: order the reducer after the whole GEMM
@@ -685,7 +723,7 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
             if ((rc = hip_fail(hipStreamWaitEvent((hipStream_t)reduce_stream, c->gemm_done, 0))) != AGG_OK) return rc;
         }
     }
-    return rs_reduce(c, Ms, N, slots, R, ldr, r_dtype, 0, reduce_stream);
+    return reduce_impl(c, Ms, N, slots, R, ldr, r_dtype, 0, reduce_stream, gemm_stream != reduce_stream);
 }
 
 // Routing + grouped GEMM, shared by ag_moe_gemm (A = T, rows gathered by token, tiles gated by the signals) and moe_rs
@@ -846,12 +884,17 @@ int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, 
     if ((rc = hip_fail(launch_topk_reduce(t, c->num_cus * 4, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
     // 3. notify: the own slot is complete; then the reducer, which waits for the peers' signals itself
     int32_t* own_flag = c->signals + (size_t)c->rank * (c->n_signals / W) * kSignalStride;
-    if ((rc = hip_fail(launch_signal_set(own_flag, c->epoch, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
+    for (int ch = 0; ch < c->rs_chunks; ++ch)   // the reduction above completes all row chunks of the slot at once
+        if ((rc = hip_fail(launch_signal_set(own_flag + ch * kSignalStride, c->epoch, (hipStream_t)gemm_stream))) != AGG_OK)
+            return rc;
     if (gemm_stream != reduce_stream) {
         bool waited = false;
         if (c->can_wait_value) {
-            waited = hipStreamWaitValue32((hipStream_t)reduce_stream, own_flag, (uint32_t)c->epoch, hipStreamWaitValueGte,
-                                          0xFFFFFFFFu) == hipSuccess;
+            // with a chunked own slot: every chunk's signal, one after the other
+            waited = true;
+            for (int ch = 0; waited && ch < c->rs_chunks; ++ch)
+                waited = hipStreamWaitValue32((hipStream_t)reduce_stream, own_flag + ch * kSignalStride, (uint32_t)c->epoch,
+                                              hipStreamWaitValueGte, 0xFFFFFFFFu) == hipSuccess;
             if (!waited) (void)hipGetLastError();
         }
         if (!waited) {

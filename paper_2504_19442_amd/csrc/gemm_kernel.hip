@@ -567,8 +567,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
 #ifdef AGG_EXP_TIMING
         const long long ttb = __builtin_readcyclecounter();
 #endif
-        // GEMM-RS: count this tile for every slice it touches; the last tile of a slice raises the slice's signal
-        // (the notify of Algorithm 3: the slice is complete where its reducer will read it)
+        // GEMM-RS: count this tile for every chunk of every slice it touches; the last tile of a chunk raises the
+        // chunk's signal (the notify of Algorithm 3: those rows are complete where their reducer will read them)
         if (!GROUPED && p.n_slices && p.slice_ctr) {
             const int w_lo = m0 / p.slice_rows, w_hi = (min(m0 + BM, p.M) - 1) / p.slice_rows;
             bool any = false;
@@ -578,15 +578,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                 __syncthreads();                 // ... and so have every other wave's, before thread 0 publishes them
                 if (tid == 0) {
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                    const int m_end = min(m0 + BM, p.M);
                     for (int w = w_lo; w <= w_hi; ++w) {
                         if (!p.slice_flag[w]) continue;
-                        // tiles that touch slice w: its m-tiles times all n-tiles
-                        const int mt_lo = (w * p.slice_rows) / BM, mt_hi = (min((w + 1) * p.slice_rows, p.M) - 1) / BM;
-                        const int target = (mt_hi - mt_lo + 1) * p.tiles_n;
-                        const int prev = __hip_atomic_fetch_add(p.slice_ctr + w, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-                        if (prev == target - 1) {
-                            __hip_atomic_store(p.slice_ctr + w, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            __hip_atomic_store(p.slice_flag[w], p.epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                        const int s0 = w * p.slice_rows;                       // first row of slice w
+                        const int c_lo = (max(m0, s0) - s0) / p.chunk_rows;
+                        const int c_hi = (min(m_end, s0 + p.slice_rows) - 1 - s0) / p.chunk_rows;
+                        for (int c = c_lo; c <= c_hi; ++c) {
+                            // tiles that touch these rows: their m-tiles times all n-tiles
+                            const int r0 = s0 + c * p.chunk_rows;
+                            const int mt_lo = r0 / BM, mt_hi = (r0 + p.chunk_rows - 1) / BM;
+                            const int target = (mt_hi - mt_lo + 1) * p.tiles_n;
+                            int* ctr = p.slice_ctr + w * p.slice_chunks + c;
+                            const int prev = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+                            if (prev == target - 1) {
+                                __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                __hip_atomic_store(p.slice_flag[w] + c * kSignalStride, p.epoch, __ATOMIC_RELEASE,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                            }
                         }
                     }
                 }

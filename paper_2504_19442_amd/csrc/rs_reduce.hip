@@ -52,11 +52,32 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
     const int W = WT > 0 ? WT : a.W;
     const long long stride = (long long)gridDim.x * 256;
     int seen = 0;                      // slots 0..seen-1 are known to have arrived (uniform over the workgroup)
+    int chunks_seen = 0;               // chunked slots: row chunks 0..chunks_seen-1 of EVERY slot have arrived
     for (long long base = (long long)blockIdx.x * 256 + tid; base - tid < a.n_vec4; base += stride * RU) {
         f32x4 acc[RU];
 #pragma unroll
         for (int u = 0; u < RU; ++u) acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (seen < W) {
+        if (a.chunks > 1) {
+            // Slots that arrive in row chunks, each chunk with a signal of its own: a workgroup walks the rows
+            // upwards, so before it enters a chunk it waits for that chunk (and any it skipped) of all W slots,
+            // and the reduction of the first chunks runs while the later ones are still being produced.
+            long long last = (base - tid) + (long long)(RU - 1) * stride + 255;
+            if (last >= a.n_vec4) last = a.n_vec4 - 1;
+            const int need = (int)(last / a.chunk_vec4);
+            if (need >= chunks_seen) {
+                int ok = 1;
+                if (tid == 0) {
+                    for (int c = chunks_seen; ok && c <= need; ++c)
+                        for (int w = 0; ok && w < W; ++w)
+                            ok = wait_signal(a.flags + ((long long)w * a.flag_step + c) * kSignalStride, a.epoch,
+                                             a.wait_ticks, a.err);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                }
+                if (__syncthreads_or(!ok)) return;
+                chunks_seen = need + 1;
+            }
+        }
+        if (a.chunks <= 1 && seen < W) {
             // slots still to arrive: take them one by one in the order of Algorithm 3.  A wait that ends also
             // looks at the signals after it, so that one acquire (an L2 invalidate) covers all that are set.
             for (int w = 0; w < W; ++w) {
@@ -121,8 +142,21 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
     }
 }
 
-hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream)
+// beside_gemm: the launch is meant to run on the same compute units as the GEMM kernel, whose waves leave 64 vector
+// registers per SIMD lane free: only kernels of at most 64 registers per lane fit there (a bigger one starts only where
+// a GEMM workgroup has finished).  All variants but <8, 2> are that small.
+hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream, bool beside_gemm)
 {
+#ifdef AGG_EXP_REDUCE_BIG
+    beside_gemm = false;
+#endif
+#ifdef AGG_EXP_REDUCE_SMALL
+    beside_gemm = true;
+#endif
+    if (a.W == 8 && beside_gemm) {
+        hipLaunchKernelGGL((reduce_kernel<8, 1>), dim3(n_workgroups), dim3(256), 0, stream, a);
+        return hipGetLastError();
+    }
     switch (a.W) {
         case 8: hipLaunchKernelGGL((reduce_kernel<8, 2>), dim3(n_workgroups), dim3(256), 0, stream, a); break;
         case 4: hipLaunchKernelGGL((reduce_kernel<4, 2>), dim3(n_workgroups), dim3(256), 0, stream, a); break;

@@ -26,6 +26,7 @@ class RsRun:
         self.W, self.rank, self.Ms, self.N = W, rank, Ms, N
         self.ctx = agg.symm_alloc(W, rank, 16, n_signals or W)
         self.step = (n_signals or W) // W
+        self.chunks = 1
         ps, cs = self.ctx.streams()
         self.prod = torch.cuda.ExternalStream(ps)
         self.cons = torch.cuda.ExternalStream(cs)
@@ -37,7 +38,13 @@ class RsRun:
             time.sleep(sleep)
         with torch.cuda.stream(self.prod):
             self.slots[w].copy_(data, non_blocking=True)
-        agg.signal_set(self.ctx, w * self.step, self.prod)
+        for c in range(self.chunks):
+            agg.signal_set(self.ctx, w * self.step + c, self.prod)
+
+    def set_chunks(self, chunks):
+        """Slots arrive (and are waited for) in this many row chunks, each with its own signal."""
+        self.chunks = chunks
+        self.ctx.set_rs_chunks(chunks)
 
     def poison(self):
         for s in self.slots:
@@ -167,17 +174,19 @@ def test_reducer_argument_errors():
 # GEMM + ReduceScatter
 # ----------------------------------------------------------------------------------------------------------------
 
-def _gemm_rs_case(shape, rank, rows_own, rows_other, tile=None, with_other=True, orders=1):
+def _gemm_rs_case(shape, rank, rows_own, rows_other, tile=None, with_other=True, orders=1, chunks=1, own_last=False):
     inp = wl.make_gemm_rs(shape, rank=rank)
     W, M, Ms, Kl, N = shape.W, shape.M, shape.Ms, shape.Kl, shape.N
     A = dev_bf16(inp.A_loc)
     B_nk = dev_bf16(np.ascontiguousarray(inp.B_kn.T))
     peers = {w: torch.from_numpy(s).cuda() for w, s in inp.peer_slots.items()}
-    run = RsRun(W, rank, Ms, N)
+    run = RsRun(W, rank, Ms, N, n_signals=W * chunks)
     results = []
     try:
         if tile is not None:
             run.ctx.set_tile_config(tile)
+        run.set_chunks(chunks)
+        run.ctx.set_rs_own_slice_last(own_last)
         others = [w for w in range(W) if w != rank]
         rng = np.random.default_rng(11)
         for k in range(orders):
@@ -238,32 +247,42 @@ def test_gemm_rs_own_slice_only():
     _gemm_rs_case(sh, 2, np.arange(sh.Ms), [], with_other=False, orders=2)
 
 
-def test_gemm_rs_full_size_sampled_rows():
+@pytest.mark.parametrize("chunks,with_other,own_last", [(2, True, False), (8, True, True), (4, False, True), (1, True, True)])
+def test_gemm_rs_tiny_with_chunk_signals(chunks, with_other, own_last):
+    sh = wl.RS_TINY
+    rank = 1
+    rows_other = [r for r in range(sh.M) if not (rank * sh.Ms <= r < (rank + 1) * sh.Ms)] if with_other else []
+    _gemm_rs_case(sh, rank, np.arange(sh.Ms), rows_other, with_other=with_other, orders=3, chunks=chunks, own_last=own_last)
+
+
+@pytest.mark.parametrize("chunks,own_last", [(1, False), (4, False), (4, True), (1, True)])
+def test_gemm_rs_full_size_sampled_rows(chunks, own_last):
     sh = wl.RS_FULL
     rank = 5
     rng = np.random.default_rng(5)
     rows_own = np.sort(rng.choice(sh.Ms, size=12, replace=False))
     rows_other = np.sort(rng.choice(np.setdiff1d(np.arange(sh.M), np.arange(rank * sh.Ms, (rank + 1) * sh.Ms)),
                                     size=12, replace=False))
-    _gemm_rs_case(sh, rank, rows_own, rows_other, orders=2)
+    _gemm_rs_case(sh, rank, rows_own, rows_other, orders=2, chunks=chunks, own_last=own_last)
 
 
 # ----------------------------------------------------------------------------------------------------------------
 # Algorithm 3 end to end: W emulated ranks on one GPU, each scattering its partial slices into the others' slots
 # ----------------------------------------------------------------------------------------------------------------
 
-def _all_ranks_gemm_rs(shape, reducers_first, tile=None, rows=None):
+def _all_ranks_gemm_rs(shape, reducers_first, tile=None, rows=None, chunks=1):
     import dataclasses
     W, M, Ms, Kl, N = shape.W, shape.M, shape.Ms, shape.Kl, shape.N
     inputs = [wl.make_gemm_rs(dataclasses.replace(shape, cfg=shape.cfg + 20 + r), rank=r) for r in range(W)]
     A = [dev_bf16(i.A_loc) for i in inputs]
     B = [dev_bf16(np.ascontiguousarray(i.B_kn.T)) for i in inputs]
-    ranks = [RsRun(W, r, Ms, N) for r in range(W)]             # slots[r][w]: rank r's slot for peer w, poisoned
+    ranks = [RsRun(W, r, Ms, N, n_signals=W * chunks) for r in range(W)]   # slots[r][w]: rank r's slot for peer w, poisoned
     R = [torch.full((Ms, N), float("nan"), device="cuda", dtype=torch.float32) for _ in range(W)]
     try:
         for rr in ranks:
             if tile is not None:
                 rr.ctx.set_tile_config(tile)
+            rr.ctx.set_rs_chunks(chunks)
             agg.signal_reset(rr.ctx)
         torch.cuda.synchronize()
 
@@ -315,6 +334,81 @@ def test_all_ranks_on_one_gpu_medium():
     sh = wl.GemmRsShape("gemm_rs_medium", 13, 4, 2048, 512, 1024)
     rows = np.sort(np.random.default_rng(2).choice(sh.M, size=64, replace=False))
     _all_ranks_gemm_rs(sh, reducers_first=False, rows=rows)
+
+
+@pytest.mark.parametrize("chunks,tile", [(2, 0), (2, 1), (4, 2), (16, 1)])
+def test_all_ranks_with_chunk_signals_tiny(chunks, tile):
+    # 64-row slices in chunks of 32, 16 or 4 rows: a tile of 128 or 256 rows completes chunks of several slices at once
+    _all_ranks_gemm_rs(wl.RS_TINY, reducers_first=False, tile=tile, chunks=chunks)
+
+
+@pytest.mark.parametrize("chunks", [2, 4])
+def test_all_ranks_with_chunk_signals_medium(chunks):
+    # 512-row slices in chunks of 256 and 128 rows (whole tiles) -- and every chunk's signal must have been raised
+    sh = wl.GemmRsShape("gemm_rs_medium", 13, 4, 2048, 512, 1024)
+    rows = np.sort(np.random.default_rng(3).choice(sh.M, size=64, replace=False))
+    _all_ranks_gemm_rs(sh, reducers_first=False, rows=rows, chunks=chunks)
+
+
+@pytest.mark.parametrize("W,Ms,N,chunks", [(4, 64, 192, 4), (8, 48, 100, 3), (3, 14, 36, 7), (2, 256, 1024, 16), (1, 6, 8, 2)])
+def test_reducer_with_chunk_signals_bit_exact_in_any_order(W, Ms, N, chunks):
+    # the slots arrive chunk by chunk in a shuffled order of (slot, chunk); the reducer, launched first, may only read
+    # what has been signalled (everything else is NaN), and the sum is the same bit for bit as with whole slots
+    data = _slots_with_cancellation(W, Ms, N, seed=7100 + W)
+    want = oracle.rs_reduce_f32(data)
+    dev = [torch.from_numpy(d).cuda() for d in data]
+    run = RsRun(W, 0, Ms, N, n_signals=W * 16)
+    cr = Ms // chunks
+    try:
+        run.ctx.set_rs_chunks(chunks)
+        rng = np.random.default_rng(5)
+        for k in range(3):
+            run.poison()
+            agg.signal_reset(run.ctx)
+            R = torch.full((Ms, N), float("nan"), device="cuda", dtype=torch.float32)
+            torch.cuda.synchronize()
+            pairs = [(w, c) for w in range(W) for c in range(chunks)]
+            rng.shuffle(pairs)
+            if k < 2:
+                agg.rs_reduce(run.ctx, Ms, N, run.slots, R, N, agg.F32, 0 if k == 0 else 3, run.cons)
+            for w, c in pairs:
+                if k == 0:
+                    time.sleep(0.001)
+                with torch.cuda.stream(run.prod):
+                    run.slots[w][c * cr:(c + 1) * cr].copy_(dev[w][c * cr:(c + 1) * cr], non_blocking=True)
+                agg.signal_set(run.ctx, w * run.step + c, run.prod)
+            if k == 2:
+                agg.rs_reduce(run.ctx, Ms, N, run.slots, R, N, agg.F32, 0, run.cons)
+            run.status_ok()
+            assert np.array_equal(R.cpu().numpy().view(np.uint32), want.view(np.uint32)), f"round {k}"
+        # shapes the chunking cannot cut are refused, and so are chunk counts beyond the signals there are
+        with pytest.raises(agg.AggError):
+            run.ctx.set_rs_chunks(17)
+        with pytest.raises(agg.AggError):
+            run.ctx.set_rs_chunks(0)
+        if Ms % 5:
+            run.ctx.set_rs_chunks(5)
+            with pytest.raises(agg.AggError):
+                agg.rs_reduce(run.ctx, Ms, N, run.slots, R, N, agg.F32, 0, run.cons)
+    finally:
+        run.close()
+
+
+def test_reducer_with_chunk_signals_times_out_on_a_missing_chunk():
+    W, Ms, N, chunks = 2, 8, 16, 2
+    run = RsRun(W, 0, Ms, N, n_signals=W * chunks)
+    try:
+        run.ctx.set_rs_chunks(chunks)
+        run.ctx.set_wait_limit_us(20000)
+        agg.signal_reset(run.ctx)
+        R = torch.zeros((Ms, N), device="cuda", dtype=torch.float32)
+        for s in (0, 1, 2):              # chunk 1 of slot 1 never arrives
+            agg.signal_set(run.ctx, s, run.prod)
+        agg.rs_reduce(run.ctx, Ms, N, run.slots, R, N, agg.F32, 0, run.cons)
+        torch.cuda.synchronize()
+        assert agg.agg_status(run.ctx) == agg.ERR_TIMEOUT
+    finally:
+        run.close()
 
 
 def test_gemm_rs_scatter_argument_errors():
