@@ -321,6 +321,29 @@ def main() -> int:
             "protocol": f"medians of 3 alternating rounds of {n3} steps",
         }
 
+        # The same step with the copy engines as producer (Section 3.6: one transfer per chunk, another per signal),
+        # for comparison with the copy kernel above: on one GPU an engine moves about 50 GB/s device to device
+        def step_sdma():
+            agg.signal_reset(ctx)
+            hev.wait(prod_h, ev_cons_done)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_SDMA | local_flag, 0, prod)
+            agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
+            hev.record(ev_cons_done, cons_h)
+
+        def step_sdma_copy():
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_SDMA | local_flag, 0, prod)
+
+        hev.record(ev_cons_done, cons_h)
+        s_fused = timed(step_sdma, 5, 2)
+        s_copy = timed(step_sdma_copy, 5, 2)
+        assert agg.agg_status(ctx) == agg.OK
+        out["copy_engine_producer"] = {
+            "t_copy_ms": round(s_copy * 1e3, 4), "t_fused_ms": round(s_fused * 1e3, 4),
+            "copy_GBps": round(shape.W * shape.Ms * K * 2 / s_copy / 1e9, 1),
+            "hidden_fraction": round((s_copy + t_gemm - s_fused) / s_copy, 4),
+            "note": "one stream, shard after shard; serial time taken as copy alone + GEMM alone",
+        }
+
         # the reducer of GEMM+ReduceScatter at its full size (all signals set: pure streaming reduction)
         rs = wl.RS_FULL
         slots = [torch.randn((rs.Ms, rs.N), device="cuda", dtype=torch.float32) for _ in range(rs.W)]

@@ -38,7 +38,9 @@ enum {
     AGG_ERR_MISALIGNED = -3,        /* a pointer or leading dimension breaks the 16-byte rule */
     AGG_ERR_HIP = -4,               /* a HIP runtime call failed (the HIP error is cleared) */
     AGG_ERR_TIMEOUT = -5,           /* a kernel gave up waiting for a signal (reported by agg_status) */
-    AGG_ERR_NOMEM = -6
+    AGG_ERR_NOMEM = -6,
+    AGG_ERR_NOT_FOUND = -7,         /* the table of tuned configurations has no entry for the problem */
+    AGG_ERR_IO = -8                 /* a file could not be opened, read or written */
 };
 
 enum { AGG_BF16 = 0, AGG_F32 = 1 };          /* element type of an output matrix */
@@ -187,6 +189,25 @@ typedef struct agg_tune_result {
 int agg_autotune_ag_gemm(agg_ctx* ctx, int M, int N, int K, const void* B, int ldb, int b_layout,
                          void* C, int ldc, int c_dtype, const void* const* remote_shards, int producer_mode,
                          int runs_per_config, agg_tune_result* out);
+
+/*
+ * Table of tuned configurations (Section 3.8: tuning results are kept and reused).  Process-wide and thread-safe; the
+ * key is (world size, M, N, K).  agg_autotune_ag_gemm enters every result it returns.  agg_tune_table_apply copies the
+ * entry for (ctx's world size, M, N, K) into the context (tile shape, tile order, producer size), as the tuner itself
+ * does at its end, or returns AGG_ERR_NOT_FOUND and leaves the context alone.  save writes the table as text (one
+ * header line, then "W M N K tile_config tile_order producer_workgroups configs_tried best_ms" per entry; lines
+ * starting with # are comments); load merges such a file into the table (entries of the file win) and returns the
+ * number of entries read, AGG_ERR_IO if the file cannot be read, or AGG_ERR_INVALID_ARG for a file with a wrong
+ * header, a malformed line or a value out of range -- the table is then left exactly as it was.  None of these calls
+ * touches the GPU.
+ */
+int agg_tune_table_size(void);
+int agg_tune_table_clear(void);
+int agg_tune_table_put(int world_size, int M, int N, int K, const agg_tune_result* entry);
+int agg_tune_table_get(int world_size, int M, int N, int K, agg_tune_result* out);
+int agg_tune_table_save(const char* path);
+int agg_tune_table_load(const char* path);
+int agg_tune_table_apply(agg_ctx* ctx, int M, int N, int K);
 
 /*
  * The GEMM half of GEMM + ReduceScatter with the scatter fused into its epilogue (Section 3.6, "Intra-node

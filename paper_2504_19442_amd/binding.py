@@ -15,7 +15,9 @@ __all__ = [
     "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "moe_rs", "agg_autotune_ag_gemm", "agg_mfma_ceiling", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
     "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL", "PRODUCER_LOCAL_LAST",
     "ORDER_ROTATED", "ORDER_SUBCHUNK", "SIGNAL_STRIDE",
-    "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM",
+    "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM", "ERR_NOT_FOUND", "ERR_IO",
+    "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load",
+    "agg_tune_table_apply", "TuneResult",
     "EXPORTS",
 ]
 
@@ -25,12 +27,13 @@ PRODUCER_KERNEL, PRODUCER_SDMA, PRODUCER_LINKS, PRODUCER_SKIP_LOCAL, PRODUCER_LO
 ORDER_ROTATED, ORDER_SUBCHUNK = 0, 1
 SIGNAL_STRIDE = 32
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT, ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
+ERR_NOT_FOUND, ERR_IO = -7, -8
 
 # every symbol include/agg.h declares
 EXPORTS = [
     "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
     "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs", "gemm_rs_scatter", "agg_autotune_ag_gemm", "agg_mfma_ceiling",
-    "ag_moe_gemm", "moe_rs", "agg_set_tile_config", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
+    "ag_moe_gemm", "moe_rs", "agg_set_tile_config", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load", "agg_tune_table_apply", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
 ]
 
 
@@ -75,6 +78,13 @@ def _lib() -> C.CDLL:
         L.rs_reduce.argtypes = [vp, i32, i32, C.POINTER(vp), vp, i32, i32, i32, vp]
         L.gemm_rs.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32, i32, C.POINTER(vp), vp, vp, i32, i32, vp, vp]
         L.gemm_rs_scatter.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32, i32, C.POINTER(vp), vp, C.POINTER(vp), i32, vp]
+        L.agg_tune_table_size.argtypes = []
+        L.agg_tune_table_clear.argtypes = []
+        L.agg_tune_table_put.argtypes = [i32, i32, i32, i32, vp]
+        L.agg_tune_table_get.argtypes = [i32, i32, i32, i32, vp]
+        L.agg_tune_table_save.argtypes = [C.c_char_p]
+        L.agg_tune_table_load.argtypes = [C.c_char_p]
+        L.agg_tune_table_apply.argtypes = [vp, i32, i32, i32]
         L.agg_autotune_ag_gemm.argtypes = [vp, i32, i32, i32, vp, i32, i32, vp, i32, i32, C.POINTER(vp), i32, i32, vp]
         L.agg_mfma_ceiling.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
         L.moe_rs.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(vp), vp, vp, i32, i32, vp, vp]
@@ -248,6 +258,46 @@ def gemm_rs_scatter(ctx: Ctx, M: int, N: int, Klocal: int, A_local, lda: int, B_
 class TuneResult(C.Structure):
     _fields_ = [("tile_config", C.c_int), ("tile_order", C.c_int), ("producer_workgroups", C.c_int),
                 ("configs_tried", C.c_int), ("best_ms", C.c_float)]
+
+
+def agg_tune_table_size() -> int:
+    return _check(_lib().agg_tune_table_size(), "agg_tune_table_size")
+
+
+def agg_tune_table_clear() -> None:
+    _check(_lib().agg_tune_table_clear(), "agg_tune_table_clear")
+
+
+def agg_tune_table_put(world_size: int, M: int, N: int, K: int, entry: TuneResult) -> None:
+    _check(_lib().agg_tune_table_put(world_size, M, N, K, C.byref(entry)), "agg_tune_table_put")
+
+
+def agg_tune_table_get(world_size: int, M: int, N: int, K: int):
+    """The entry, or None where the table has none."""
+    res = TuneResult()
+    rc = _lib().agg_tune_table_get(world_size, M, N, K, C.byref(res))
+    if rc == ERR_NOT_FOUND:
+        return None
+    _check(rc, "agg_tune_table_get")
+    return res
+
+
+def agg_tune_table_save(path: str) -> None:
+    _check(_lib().agg_tune_table_save(os.fsencode(path)), "agg_tune_table_save")
+
+
+def agg_tune_table_load(path: str) -> int:
+    """Merges the file into the table; returns the number of entries read."""
+    return _check(_lib().agg_tune_table_load(os.fsencode(path)), "agg_tune_table_load")
+
+
+def agg_tune_table_apply(ctx: Ctx, M: int, N: int, K: int) -> bool:
+    """True if the context now carries the table's entry for this problem, False if there is none."""
+    rc = _lib().agg_tune_table_apply(ctx.handle, M, N, K)
+    if rc == ERR_NOT_FOUND:
+        return False
+    _check(rc, "agg_tune_table_apply")
+    return True
 
 
 def agg_autotune_ag_gemm(ctx: Ctx, M: int, N: int, K: int, B, ldb: int, b_layout: int, Cout, ldc: int, c_dtype: int,

@@ -142,6 +142,7 @@ struct ReduceArgs {
     long long wait_ticks;
     int* err;
 };
+void tune_table_put(int W, int M, int N, int K, const agg_tune_result& r);   // the process-wide table of tuned configurations
 hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream, bool beside_gemm);
 
 }  // namespace agg

@@ -580,6 +580,7 @@ int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb
     c->tile_config = res.tile_config;
     c->tile_order = res.tile_order;
     c->producer_wgs = res.producer_workgroups;
+    tune_table_put(c->W, M, N, K, res);
     *out = res;
     return AGG_OK;
 }
@@ -924,6 +925,8 @@ const char* agg_strerror(int code)
         case AGG_ERR_HIP: return "HIP runtime error";
         case AGG_ERR_TIMEOUT: return "a kernel gave up waiting for a signal";
         case AGG_ERR_NOMEM: return "out of memory";
+        case AGG_ERR_NOT_FOUND: return "no such entry";
+        case AGG_ERR_IO: return "file could not be read or written";
         default: return "unknown error";
     }
 }

@@ -392,8 +392,19 @@ def test_autotuner_runs_the_whole_function_and_leaves_a_working_configuration():
         with pytest.raises(agg.AggError):
             agg.agg_autotune_ag_gemm(run.ctx, sh.M, sh.N, sh.K + 8, run.B_nk, sh.K, agg.B_NK, C, sh.N, agg.F32, run.remote,
                                      agg.PRODUCER_KERNEL, 1)
+        # the tuner's results are kept: the table holds the latest one for this problem, and a new context takes it over
+        ent = agg.agg_tune_table_get(sh.W, sh.M, sh.N, sh.K)
+        assert (ent.tile_config, ent.tile_order, ent.producer_workgroups) == (res2.tile_config, res2.tile_order, 0)
+        other = AgGemmRun(inp, 1, chunks_per_shard=2)
+        try:
+            assert agg.agg_tune_table_apply(other.ctx, sh.M, sh.N, sh.K)
+            assert not agg.agg_tune_table_apply(other.ctx, sh.M, sh.N, sh.K + 64)
+            check_f32(other.run().cpu().numpy(), want, sh.K)
+        finally:
+            other.close()
     finally:
         run.close()
+        agg.agg_tune_table_clear()
 
 
 @pytest.mark.parametrize("K", [64, 192, 448, 960])

@@ -411,6 +411,48 @@ def test_reducer_with_chunk_signals_times_out_on_a_missing_chunk():
         run.close()
 
 
+@pytest.mark.parametrize("chunks", [1, 2])
+def test_all_ranks_pull_mode(chunks):
+    # Pull mode (Section 3.5 names both): every rank keeps its whole partial product P_w at home and only notifies;
+    # rank r's reducer reads slice r of every P_w in place.  Same kernels, other pointers: no slice has a destination of
+    # its own (all go to P_other = P_w), signal (r, w) is raised by rank w's GEMM, and the reducer's slots point into
+    # the peers' P buffers.
+    import dataclasses
+    sh = wl.RS_TINY
+    W, M, Ms, Kl, N = sh.W, sh.M, sh.Ms, sh.Kl, sh.N
+    inputs = [wl.make_gemm_rs(dataclasses.replace(sh, cfg=sh.cfg + 40 + r), rank=r) for r in range(W)]
+    A = [dev_bf16(i.A_loc) for i in inputs]
+    B = [dev_bf16(np.ascontiguousarray(i.B_kn.T)) for i in inputs]
+    ranks = [RsRun(W, r, Ms, N, n_signals=W * chunks) for r in range(W)]
+    P = [torch.full((M, N), float("nan"), device="cuda", dtype=torch.float32) for _ in range(W)]
+    R = [torch.full((Ms, N), float("nan"), device="cuda", dtype=torch.float32) for _ in range(W)]
+    try:
+        for rr in ranks:
+            rr.set_chunks(chunks)
+            agg.signal_reset(rr.ctx)
+        torch.cuda.synchronize()
+        for w, rw in enumerate(ranks):
+            sig = [ranks[r].ctx.signals + (w * ranks[r].step) * agg.SIGNAL_STRIDE * 4 for r in range(W)]
+            agg.gemm_rs_scatter(rw.ctx, M, N, Kl, A[w], Kl, B[w], Kl, agg.B_NK, [None] * W, P[w], sig, (w + 1) % W, rw.prod)
+        for r, rr in enumerate(ranks):
+            pulled = [P[w][r * Ms:(r + 1) * Ms] for w in range(W)]
+            agg.rs_reduce(rr.ctx, Ms, N, pulled, R[r], N, agg.F32, 0, rr.cons)
+        for rr in ranks:
+            rr.status_ok()
+        for r in range(W):
+            parts = [P[w][r * Ms:(r + 1) * Ms].cpu().numpy() for w in range(W)]
+            assert np.array_equal(oracle.rs_reduce_f32(parts).view(np.uint32), R[r].cpu().numpy().view(np.uint32))
+        A_cat = np.concatenate([i.A_loc for i in inputs], axis=1)
+        B_cat = np.concatenate([i.B_kn for i in inputs], axis=0)
+        got = torch.cat(R).cpu().numpy().astype(np.float64)
+        want = oracle.gemm(A_cat, B_cat)
+        assert np.linalg.norm(got - want) / np.linalg.norm(want) <= 1e-4
+        assert np.abs(got - want).max() <= 1e-3 * np.sqrt(W * Kl) * max(1.0, float(np.abs(want).max()))
+    finally:
+        for rr in ranks:
+            rr.close()
+
+
 def test_gemm_rs_scatter_argument_errors():
     sh = wl.RS_TINY
     run = RsRun(sh.W, 0, sh.Ms, sh.N)
