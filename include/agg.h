@@ -318,9 +318,9 @@ int moe_rs(agg_ctx* ctx, int Ttok, int topk, int E, int N, int Klocal,
            const float* const* slots, float* Z_other, void* R, int ldr, int r_dtype,
            void* gemm_stream, void* reduce_stream);
 
-/* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 128x128,
- * 2 = 256x256.  A tuning knob (Section 3.8); every shape gives the same result (the sum over K runs in the same
- * order in all of them). */
+/* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default; never 3), 0 = 256x224, 1 = 128x128,
+ * 2 = 256x256, 3 = 128x256.  A tuning knob (Section 3.8); every shape gives the same result (the sum over K runs in
+ * the same order in all of them). */
 int agg_set_tile_config(agg_ctx* ctx, int tile_config);
 
 /*

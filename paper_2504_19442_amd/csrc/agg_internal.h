@@ -88,7 +88,7 @@ struct TopkReduceArgs {
 hipError_t launch_topk_reduce(const TopkReduceArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream_t stream);
 
-enum TileConfig { TILE_256x224 = 0, TILE_128x128 = 1, TILE_256x256 = 2, TILE_CONFIGS };
+enum TileConfig { TILE_256x224 = 0, TILE_128x128 = 1, TILE_256x256 = 2, TILE_128x256 = 3, TILE_CONFIGS };
 
 struct TileShape { int bm, bn; };
 inline TileShape tile_shape(int cfg)
@@ -96,6 +96,7 @@ inline TileShape tile_shape(int cfg)
     switch (cfg) {
         case TILE_256x224: return {256, 224};
         case TILE_256x256: return {256, 256};
+        case TILE_128x256: return {128, 256};
         default: return {128, 128};
     }
 }

@@ -110,7 +110,7 @@ struct Cfg {
 #ifndef AGG_RING_BIG
 #define AGG_RING_BIG 35
 #endif
-    static constexpr int RW = (BM == 256 && BN == 256) ? 36 : (BM == 256) ? AGG_RING_BIG : 32;
+    static constexpr int RW = (BN == 256) ? 36 : (BM == 256) ? AGG_RING_BIG : 32;
     static constexpr int RING_BYTES = RW * 4096;
     static constexpr int PERIOD = std::lcm(L, RW) / L;     // stages after which ring positions repeat
     // epilogue staging: each wave stages 32 rows x BN columns at a time
@@ -641,6 +641,7 @@ hipError_t launch_gemm(const GemmParams& p, int cfg, int grid, hipStream_t strea
     switch (cfg) {
         case TILE_256x224: return launch_cfg<256, 224, false>(p, grid, stream);
         case TILE_256x256: return launch_cfg<256, 256, false>(p, grid, stream);
+        case TILE_128x256: return launch_cfg<128, 256, false>(p, grid, stream);
         default: return launch_cfg<128, 128, false>(p, grid, stream);
     }
 }
@@ -650,6 +651,7 @@ hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream
     switch (cfg) {
         case TILE_256x224: return launch_cfg<256, 224, true>(p, grid, stream);
         case TILE_256x256: return launch_cfg<256, 256, true>(p, grid, stream);
+        case TILE_128x256: return launch_cfg<128, 256, true>(p, grid, stream);
         default: return launch_cfg<128, 128, true>(p, grid, stream);
     }
 }

@@ -62,7 +62,7 @@ def test_tiny_bit_identical_over_all_arrival_orders_and_launch_orders():
         run.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
 def test_integer_inputs_are_exact(tile):
     # entries in {-2..2}: every partial sum is an integer below 2^24, so fp32 accumulation is exact
     inp = wl.make_ag_gemm(wl.AG_RAGGED, a_dist=("int", 2), b_dist=("int", 2))
@@ -87,7 +87,7 @@ def test_identity_b_returns_gathered_a_bit_exactly():
         run.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
 @pytest.mark.parametrize("chunks", [1, 4])
 def test_ragged_shape_f32_and_bf16(tile, chunks):
     inp = wl.make_ag_gemm(wl.AG_RAGGED)         # M=600, N=328, K=320: ragged against every tile shape
@@ -333,7 +333,7 @@ def test_world_of_one_is_a_plain_gemm():
     assert np.array_equal(want, oracle.ag_gemm(inp.shards, inp.B_kn, 0))
     run = AgGemmRun(inp, 0)
     try:
-        for tile in (0, 1, 2):
+        for tile in (0, 1, 2, 3):
             check_f32(run.run(tile=tile).cpu().numpy(), want, sh.K)
     finally:
         run.close()
@@ -415,7 +415,7 @@ def test_short_and_odd_k_ranges(K):
     want = oracle.ag_gemm(inp.shards, inp.B_kn, 1)
     run = AgGemmRun(inp, 1)
     try:
-        for tile in (0, 1, 2):
+        for tile in (0, 1, 2, 3):
             C = run.run(tile=tile).cpu().numpy()
             assert np.array_equal(C.astype(np.float64), want), (K, tile)      # integer inputs: exact
     finally:
@@ -460,7 +460,7 @@ def test_seeded_random_shapes_and_settings_exact():
         K = 64 * int(rng.integers(1, 12))
         N = int(rng.choice([8, 24, 100, 101, 128, 222, 224, 232, 256, 257, 300, 448, 520, 736]))
         rank = int(rng.integers(0, W))
-        tile = int(rng.choice([-1, 0, 1, 2]))
+        tile = int(rng.choice([-1, 0, 1, 2, 3]))
         order = int(rng.choice([agg.ORDER_ROTATED, agg.ORDER_SUBCHUNK]))
         mode = int(rng.choice([agg.PRODUCER_KERNEL, agg.PRODUCER_LINKS, agg.PRODUCER_SDMA]))
         local = bool(rng.integers(0, 2))

@@ -70,7 +70,7 @@ def _check_y(Y, want, K, scale=1.0):
 
 
 @pytest.mark.parametrize("rank", [0, 2])
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
 def test_moe_tiny_against_oracle(rank, tile):
     sh = wl.MOE_TINY
     inp = wl.make_moe(sh)
@@ -109,6 +109,30 @@ def test_moe_integer_inputs_exact_and_several_signals_per_shard():
     run = MoeRun(inp, 1, chunks_per_shard=4)
     try:
         Y, _, _ = run.run()
+        assert np.array_equal(Y.cpu().numpy().astype(np.float64), want)
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("tile", [0, 2, 3])
+def test_moe_segments_with_full_blocks_and_short_tails(tile):
+    # 640 tokens x top-2 over 5 experts, 150 pairs moved from expert 4 to expert 3.  Rows per expert: 276 and 261 (a full
+    # 256-row block and a short tail for the 128-row launch), 242 (one 256-row tile), 399 (a full block and a tail of
+    # 143 rows), 102 (less than half a tile).  Integer inputs: the result is exact.
+    sh = wl.MoeShape("moe_blocks", 17, 2, 320, 128, 320, 5, 2)
+    inp = wl.make_moe(sh, x_dist=("int", 2), w_dist=("int", 2))
+    ids = inp.topk_ids.copy()
+    for col in (0, 1):
+        move = np.nonzero((ids[:, col] == 4) & (ids[:, 1 - col] != 3))[0][:75]
+        ids[move, col] = 3
+    inp = wl.MoeInputs(sh, inp.shards, inp.W_ekn, np.ascontiguousarray(ids))
+    counts = np.bincount(ids.reshape(-1), minlength=sh.E)
+    assert list(counts) == [276, 242, 261, 399, 102], counts
+    want = oracle.moe_gemm(inp.shards, inp.W_ekn, inp.topk_ids, 1)
+    run = MoeRun(inp, 1, chunks_per_shard=2)
+    try:
+        Y, tok, seg = run.run(tile=tile)
+        assert np.array_equal(np.diff(seg), counts)
         assert np.array_equal(Y.cpu().numpy().astype(np.float64), want)
     finally:
         run.close()

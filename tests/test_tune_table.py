@@ -33,7 +33,7 @@ def test_put_get_and_missing_entries():
     assert agg.agg_tune_table_get(8, 8192, 7168, 4096) is None
 
 
-@pytest.mark.parametrize("bad", [dict(tile=3), dict(tile=-1), dict(order=2), dict(wgs=-1), dict(wgs=5000), dict(ms=-1.0)])
+@pytest.mark.parametrize("bad", [dict(tile=4), dict(tile=-1), dict(order=2), dict(wgs=-1), dict(wgs=5000), dict(ms=-1.0)])
 def test_put_rejects_values_out_of_range(bad):
     with pytest.raises(agg.AggError) as e:
         agg.agg_tune_table_put(8, 64, 64, 64, _entry(**bad))
