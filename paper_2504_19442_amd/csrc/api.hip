@@ -490,10 +490,10 @@ static int reduce_impl(agg_ctx* c, int Ms, int N, const float* const* slots, voi
     a.err = c->err;
     int nwg = n_workgroups;
     if (nwg == 0) {
-        // persistent: two workgroups per CU (measured best: 5.5 TB/s against 5.1 with four), each walking many
-        // blocks (one acquire per workgroup, not per block)
+        // persistent: one workgroup per CU (measured: 6.27 TB/s with 1 or 1.5 per CU, 6.05 with two, 5.6 with three),
+        // each walking many blocks (one acquire per workgroup, not per block)
         const long long need = (a.n_vec4 + 255) / 256;
-        nwg = (int)(need < (long long)c->num_cus * 2 ? need : (long long)c->num_cus * 2);
+        nwg = (int)(need < (long long)c->num_cus ? need : (long long)c->num_cus);
         if (nwg < 1) nwg = 1;
     }
     return hip_fail(launch_reduce(a, nwg, (hipStream_t)stream, beside_gemm));

@@ -4,6 +4,10 @@
 // registers, so its waves fit beside the consumer's on any CU (Section 3.8, resource partition).
 #include "agg_internal.h"
 
+#ifndef AGG_PROD_LOAD_AUX
+#define AGG_PROD_LOAD_AUX 2          // cache policy bits of the copy's loads: 2 = nt (streaming)
+#endif
+
 namespace agg {
 
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
@@ -32,7 +36,7 @@ __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
     // cache policy bits: loads nt (streaming); stores sc1 = agent scope, written through this XCD's L2 so that the
     // consumer's XCDs find the data in memory (system scope or streaming stores were measured slightly slower
     // beside the GEMM)
-    constexpr int NT = 2, WT = 16;
+    constexpr int NT = AGG_PROD_LOAD_AUX, WT = 16;
     for (int ch = t; ch < n_chunks; ch += n_teams) {
         const int job = ch / a.chunks_per_shard, c = ch - job * a.chunks_per_shard;
         const int r = a.rank_of[job];
@@ -86,7 +90,7 @@ __global__ __launch_bounds__(256) void producer_links_kernel(const ProducerArgs 
     const long long lo = j * per_wg, hi = lo + per_wg < vec_per_chunk ? lo + per_wg : vec_per_chunk;
     const unsigned bytes = hi > lo ? (unsigned)((hi - lo) * 16) : 0u;
     const int r = a.rank_of[link];
-    constexpr int NT = 2, WT = 16;
+    constexpr int NT = AGG_PROD_LOAD_AUX, WT = 16;
     for (int c = 0; c < a.chunks_per_shard; ++c) {
         const char* s = (const char*)a.src[link] + (c * vec_per_chunk + lo) * 16;
         char* d = a.T + (long long)r * a.shard_bytes + (c * vec_per_chunk + lo) * 16;
