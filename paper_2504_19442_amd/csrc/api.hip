@@ -490,10 +490,12 @@ static int reduce_impl(agg_ctx* c, int Ms, int N, const float* const* slots, voi
     a.err = c->err;
     int nwg = n_workgroups;
     if (nwg == 0) {
-        // persistent: one workgroup per CU (measured: 6.27 TB/s with 1 or 1.5 per CU, 6.05 with two, 5.6 with three),
-        // each walking many blocks (one acquire per workgroup, not per block)
+        // persistent: three workgroups per two CUs, each walking many blocks (one acquire per workgroup, not per
+        // block).  Measured: 6.2 TB/s; one per CU reaches 6.27 alone but 5.8 when the placement of the workgroups
+        // is less than perfect (as found inside longer runs); two per CU 6.1, three 5.3.
         const long long need = (a.n_vec4 + 255) / 256;
-        nwg = (int)(need < (long long)c->num_cus ? need : (long long)c->num_cus);
+        const long long want = (long long)c->num_cus * 3 / 2;
+        nwg = (int)(need < want ? need : want);
         if (nwg < 1) nwg = 1;
     }
     return hip_fail(launch_reduce(a, nwg, (hipStream_t)stream, beside_gemm));
