@@ -494,7 +494,8 @@ static int reduce_impl(agg_ctx* c, int Ms, int N, const float* const* slots, voi
         // block).  Measured: 6.2 TB/s; one per CU reaches 6.27 alone but 5.8 when the placement of the workgroups
         // is less than perfect (as found inside longer runs); two per CU 6.1, three 5.3.
         const long long need = (a.n_vec4 + 255) / 256;
-        const long long want = (long long)c->num_cus * 3 / 2;
+        // Beside the GEMM a CU has room for one reducer workgroup only (one 64-register wave per SIMD).
+        const long long want = beside_gemm ? (long long)c->num_cus : (long long)c->num_cus * 3 / 2;
         nwg = (int)(need < want ? need : want);
         if (nwg < 1) nwg = 1;
     }
