@@ -862,6 +862,7 @@ int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, 
     if (Kl == 0 || Kl % 64 != 0 || Kl > (1 << 21) || N % 4 != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
     const int W = c->W, Tr = Ttok / W;
     // the reduction's arguments, checked before anything is enqueued
+    if (Tr % c->rs_chunks != 0) return AGG_ERR_UNSUPPORTED_SHAPE;      // (N % 4 == 0 makes every chunk whole float4s)
     if (!R || ldr < N || (r_dtype != AGG_BF16 && r_dtype != AGG_F32)) return AGG_ERR_INVALID_ARG;
     if (ldr != N && ldr % 4 != 0) return AGG_ERR_MISALIGNED;
     for (int w = 0; w < W; ++w)

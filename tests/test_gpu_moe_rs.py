@@ -12,14 +12,16 @@ pytestmark = pytest.mark.gpu
 
 
 class MoeRsRun:
-    def __init__(self, inp, rank):
+    def __init__(self, inp, rank, chunks=1):
         sh = inp.shape
         self.inp, self.sh, self.rank = inp, sh, rank
         self.H = dev_bf16(inp.H)
         self.W2 = dev_bf16(np.ascontiguousarray(np.transpose(inp.W2_ekn, (0, 2, 1))))      # [E][N][Kl]
         self.ids = torch.from_numpy(inp.topk_ids).cuda()
         self.gate = torch.from_numpy(inp.gate).cuda()
-        self.ctx = agg.symm_alloc(sh.W, rank, 16, sh.W)
+        self.chunks = chunks
+        self.ctx = agg.symm_alloc(sh.W, rank, 16, sh.W * chunks)
+        self.ctx.set_rs_chunks(chunks)
         ps, cs = self.ctx.streams()
         self.prod, self.cons = torch.cuda.ExternalStream(ps), torch.cuda.ExternalStream(cs)
         P = sh.T * sh.topk
@@ -48,7 +50,8 @@ class MoeRsRun:
             for w in sorted(self.peers, reverse=True):
                 with torch.cuda.stream(self.prod):
                     self.slots[w].copy_(self.peers[w], non_blocking=True)
-                agg.signal_set(self.ctx, w, self.prod)
+                for c in range(self.chunks):
+                    agg.signal_set(self.ctx, w * self.chunks + c, self.prod)
 
         if peers_first:
             deliver()
@@ -117,15 +120,20 @@ def test_moe_rs_tiny(rank, tile):
         run.close()
 
 
-def test_moe_rs_integer_inputs_exact():
+@pytest.mark.parametrize("chunks", [1, 4])
+def test_moe_rs_integer_inputs_exact(chunks):
     sh = wl.MoeRsShape("moe_rs_int", 18, 2, 40, 128, 40, 7, 2)
     inp = wl.make_moe_rs(sh, rank=1, h_dist=("int", 2), w_dist=("int", 2), slot_dist=("int", 3))
     inp.gate[:] = np.float32(0.5)                     # halves: every product and sum below is exact in fp32
     want = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, inp.peer_slots, sh.W, 1)
-    run = MoeRsRun(inp, 1)
+    run = MoeRsRun(inp, 1, chunks=chunks)       # with chunks: every slot is signalled in four row chunks of 10 tokens
     try:
         R, _ = run.run(False)
         assert np.array_equal(R.cpu().numpy().astype(np.float64), want)
+        if chunks > 1:
+            run.ctx.set_rs_chunks(3)             # 40 tokens per rank do not cut into 3 chunks: refused before any launch
+            with pytest.raises(agg.AggError):
+                run.run(False)
     finally:
         run.close()
 
