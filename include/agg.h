@@ -151,6 +151,8 @@ int ag_gemm(agg_ctx* ctx, int M, int N, int K,
  * (copies, signal_set and this library's producer can; a kernel that needs every register of a CU cannot).
  * slots: HOST array of W device pointers to fp32 [Ms, N] row-major (leading dimension N).
  * R: [Ms, N] of r_dtype, leading dimension ldr.  Ms * N must be a multiple of 4; slots 16-byte aligned.
+ * n_workgroups: size of the (persistent) grid, 0 = the library's choice (three workgroups per two compute units).
+ * With agg_set_rs_chunks(k > 1) the wait is per row chunk of a slot instead (see there).
  */
 int rs_reduce(agg_ctx* ctx, int Ms, int N, const float* const* slots,
               void* R, int ldr, int r_dtype, int n_workgroups, void* stream);
