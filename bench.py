@@ -344,6 +344,32 @@ def main() -> int:
             "note": "one stream, shard after shard; serial time taken as copy alone + GEMM alone",
         }
 
+        # The fused step recorded once in a HIP graph (the epoch kept on the device, so that every replay is a run
+        # with fresh signals) and replayed: what a serving loop that cannot afford the launches would do
+        ctx.set_device_epoch(True)
+        s0 = torch.cuda.Stream()
+
+        def enqueue_run():
+            agg.signal_reset(ctx, s0)
+            prod.wait_stream(s0)
+            cons.wait_stream(s0)
+            agg.ag_producer_emulate(ctx, run.remote, None, agg.PRODUCER_KERNEL | local_flag, args.producer_wgs, prod)
+            agg.ag_gemm(ctx, M, N, K, run.B_nk, K, agg.B_NK, C, N, agg.BF16, cons)
+            s0.wait_stream(prod)
+            s0.wait_stream(cons)
+
+        with torch.cuda.stream(s0):
+            enqueue_run()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s0, capture_error_mode="thread_local"):
+            enqueue_run()
+        t_graph = timed(graph.replay, n2 * 2, 5)
+        assert agg.agg_status(ctx) == agg.OK, "a wait timed out in a graph replay"
+        ctx.set_device_epoch(False)
+        out["graph_replay"] = {"ms_per_replay": round(t_graph * 1e3, 4), "tflops": round(flops / t_graph / 1e12, 2),
+                               "note": "signal_reset + producer + gated GEMM + join as one HIP graph"}
+
         # the reducer of GEMM+ReduceScatter at its full size (all signals set: pure streaming reduction)
         rs = wl.RS_FULL
         slots = [torch.randn((rs.Ms, rs.N), device="cuda", dtype=torch.float32) for _ in range(rs.W)]

@@ -89,10 +89,26 @@ int symm_streams(agg_ctx* ctx, void** producer_stream, void** consumer_stream);
 /*
  * "Reset all the signals" before every run of an overlapped function (Section 3.8, the autotuner's rule).
  * Advances the epoch; calls issued afterwards wait for, and set, the new epoch.  The caller orders the
- * previous run's kernels before the next run's producer (they share T).  `stream` is accepted for
- * interface stability and unused.
+ * previous run's kernels before the next run's producer (they share T).  `stream` is used only with
+ * agg_set_device_epoch(ctx, 1).
  */
 int signal_reset(agg_ctx* ctx, void* stream);
+
+/*
+ * Where the epoch lives.  0 (default): on the host; every launch takes the epoch as an argument when it is enqueued,
+ * and signal_reset is host work only.  1: in a device word; signal_reset enqueues a one-thread kernel on `stream`
+ * that advances it, and every kernel of this library (producers, signal_set, the GEMMs, the reducer) reads the epoch
+ * from that word when it STARTS.  The caller then orders signal_reset before the launches of the run on their streams
+ * (an event from the reset's stream to the producer's and the consumer's), and a whole run -- reset, arrival, gated
+ * GEMM, join -- can be recorded into a HIP graph by stream capture and replayed: every replay is a run with a fresh
+ * epoch.  (With the epoch on the host a replay would compare the signals with the epoch of the recording, which the
+ * first run has already reached.)  Nothing this library enqueues for a run is a memset or an allocation; the first
+ * ag_gemm of a tile shape sets a function attribute and ag_moe_gemm / AGG_B_KN allocate on first use, so run once
+ * before recording.  In this mode gemm_rs and moe_rs order their reducer behind the whole GEMM with an event (a stream
+ * wait on memory compares with a value fixed at enqueue time).  symm_epoch keeps counting the host's resets and does
+ * not see replays.  Synchronises the device.
+ */
+int agg_set_device_epoch(agg_ctx* ctx, int on);
 
 /* Set signal `index` to the current epoch on `stream` (a 4-byte release store by a one-thread kernel). */
 int signal_set(agg_ctx* ctx, int index, void* stream);

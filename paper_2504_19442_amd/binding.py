@@ -33,7 +33,7 @@ ERR_NOT_FOUND, ERR_IO = -7, -8
 EXPORTS = [
     "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
     "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs", "gemm_rs_scatter", "agg_autotune_ag_gemm", "agg_mfma_ceiling",
-    "ag_moe_gemm", "moe_rs", "agg_set_tile_config", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load", "agg_tune_table_apply", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
+    "ag_moe_gemm", "moe_rs", "agg_set_tile_config", "agg_set_device_epoch", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load", "agg_tune_table_apply", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
 ]
 
 
@@ -68,6 +68,7 @@ def _lib() -> C.CDLL:
         L.agg_set_wait_limit_us.argtypes = [vp, u64]
         L.agg_set_tile_config.argtypes = [vp, i32]
         L.agg_set_tile_order.argtypes = [vp, i32]
+        L.agg_set_device_epoch.argtypes = [vp, i32]
         L.agg_set_rs_chunks.argtypes = [vp, i32]
         L.agg_set_rs_own_slice_last.argtypes = [vp, i32]
         L.agg_set_local_shard.argtypes = [vp, vp]
@@ -171,6 +172,9 @@ class Ctx:
 
     def set_rs_own_slice_last(self, on: bool) -> None:
         _check(_lib().agg_set_rs_own_slice_last(self.handle, 1 if on else 0), "agg_set_rs_own_slice_last")
+
+    def set_device_epoch(self, on: bool) -> None:
+        _check(_lib().agg_set_device_epoch(self.handle, 1 if on else 0), "agg_set_device_epoch")
 
     def set_rs_chunks(self, chunks: int) -> None:
         _check(_lib().agg_set_rs_chunks(self.handle, int(chunks)), "agg_set_rs_chunks")

@@ -34,6 +34,7 @@ struct GemmParams {
     // signals (nullptr = un-gated)
     const int* flags;
     int epoch;
+    const int* epoch_ptr;         // not null: the epoch is read from this device word when the kernel starts
     int rows_per_flag;    // rows of A covered by one signal
     int n_flags;
     long long wait_ticks; // bound of a wait, in wall-clock ticks
@@ -114,13 +115,15 @@ struct ProducerArgs {
     int* flags;
     int* counters;
     int epoch;
+    const int* epoch_ptr;         // not null: the epoch is read from this device word when the kernel starts
     int team;                     // workgroups that share one chunk (set by launch_producer)
     int link_wgs;                 // full-mesh mode: workgroups per link (set by launch_producer_links)
     double ticks_per_byte;        // full-mesh mode: wall-clock ticks a link takes per byte (0 = not paced)
 };
 hipError_t launch_producer(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_producer_links(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
-hipError_t launch_signal_set(int* flag, int value, hipStream_t stream);
+hipError_t launch_signal_set(int* flag, int value, const int* value_ptr, hipStream_t stream);
+hipError_t launch_epoch_advance(int* epoch_word, hipStream_t stream);
 hipError_t launch_signal_probe(const int* flag, int value, long long ticks, int* seen, hipStream_t stream);
 
 hipError_t launch_transpose_kn(const uint16_t* B_kn, long long ldb, int K, int N, uint16_t* B_nk, hipStream_t stream);
@@ -140,6 +143,7 @@ struct ReduceArgs {
     int chunks;                   // > 1: slot w arrives in this many row chunks, chunk c on signal w * flag_step + c
     long long chunk_vec4;         // float4 elements per chunk
     int epoch;
+    const int* epoch_ptr;         // not null: the epoch is read from this device word when the kernel starts
     long long wait_ticks;
     int* err;
 };
@@ -160,7 +164,8 @@ struct agg_ctx {
     int* signals;        // S, n_signals * stride
     int* counters;       // per-signal arrival counters (producer), + GEMM-RS tile counter
     int* err;            // time-out record
-    int* epoch_word;     // device copy of the epoch (source of the SDMA signal copies)
+    int* epoch_word;     // device copy of the epoch (source of the SDMA signal copies; the epoch itself in device-epoch mode)
+    int device_epoch;    // 1: launches read the epoch from epoch_word when they start (HIP graph replay)
     int device;
     int tile_config;     // -1 = automatic
     int tile_order;      // AGG_ORDER_*

@@ -126,7 +126,7 @@ int pick_concurrent_stream(agg_ctx* c)
         if ((rc = hip_fail(hipMemset(word, 0, 2 * sizeof(int)))) != AGG_OK) break;
         if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) break;
         if ((rc = hip_fail(launch_signal_probe(word, 1, c->wall_khz / 2, word + 1, c->consumer_stream))) != AGG_OK) break;
-        if ((rc = hip_fail(launch_signal_set(word, 1, cand[i]))) != AGG_OK) break;
+        if ((rc = hip_fail(launch_signal_set(word, 1, nullptr, cand[i]))) != AGG_OK) break;
         if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) break;
         int seen = 0;
         if ((rc = hip_fail(hipMemcpy(&seen, word + 1, sizeof seen, hipMemcpyDeviceToHost))) != AGG_OK) break;
@@ -230,18 +230,41 @@ int symm_streams(agg_ctx* c, void** producer_stream, void** consumer_stream)
     return AGG_OK;
 }
 
-int signal_reset(agg_ctx* c, void* /*stream*/)
+int signal_reset(agg_ctx* c, void* stream)
 {
     if (!c) return AGG_ERR_INVALID_ARG;
     if (c->epoch >= 0x7ffffff0) return AGG_ERR_INVALID_ARG;   // 2^31 runs: allocate a new context
+    // with the epoch kept on the device, the reset is a one-thread kernel on the caller's stream (a HIP graph can
+    // record it, and every replay advances the epoch); the host's count of resets is kept as well
+    if (c->device_epoch) {
+        const int rc = hip_fail(launch_epoch_advance(c->epoch_word, (hipStream_t)stream));
+        if (rc != AGG_OK) return rc;
+    }
     c->epoch += 1;
+    return AGG_OK;
+}
+
+int agg_set_device_epoch(agg_ctx* c, int on)
+{
+    if (!c || (on != 0 && on != 1)) return AGG_ERR_INVALID_ARG;
+    // both directions start from a quiet device: the word and the host's count are made equal
+    HIP_TRY(hipDeviceSynchronize());
+    if (on) {
+        HIP_TRY(hipMemcpy(c->epoch_word, &c->epoch, sizeof(int), hipMemcpyHostToDevice));
+    } else if (c->device_epoch) {
+        int e = 0;
+        HIP_TRY(hipMemcpy(&e, c->epoch_word, sizeof(int), hipMemcpyDeviceToHost));
+        if (e > c->epoch) c->epoch = e;       // replays of a graph advanced the device's count past the host's
+    }
+    c->device_epoch = on;
     return AGG_OK;
 }
 
 int signal_set(agg_ctx* c, int index, void* stream)
 {
     if (!c || index < 0 || index >= c->n_signals) return AGG_ERR_INVALID_ARG;
-    return hip_fail(launch_signal_set(c->signals + (size_t)index * kSignalStride, c->epoch, (hipStream_t)stream));
+    return hip_fail(launch_signal_set(c->signals + (size_t)index * kSignalStride, c->epoch,
+                                      c->device_epoch ? c->epoch_word : nullptr, (hipStream_t)stream));
 }
 
 int agg_set_wait_limit_us(agg_ctx* c, uint64_t us)
@@ -347,6 +370,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     a.flags = c->signals;
     a.counters = c->counters;
     a.epoch = c->epoch;
+    a.epoch_ptr = c->device_epoch ? c->epoch_word : nullptr;
     hipStream_t st = (hipStream_t)producer_stream;
     // a workgroup addresses its part of a chunk with 32-bit offsets
     if (mode != AGG_PRODUCER_SDMA) {
@@ -388,7 +412,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
         return hip_fail(launch_producer(loc, nwg, st));
     }
     // copy engine: one transfer per chunk, then "another data transfer solely for signals" (Section 3.6)
-    HIP_TRY(launch_signal_set(c->epoch_word, c->epoch, st));
+    if (!c->device_epoch) HIP_TRY(launch_signal_set(c->epoch_word, c->epoch, nullptr, st));   // else the word is the epoch already
     for (int j = 0; j < a.n_jobs; ++j) {
         const int r = a.rank_of[j];
         for (int ch = 0; ch < cps; ++ch) {
@@ -444,6 +468,7 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     }
     p.flags = c->signals;
     p.epoch = c->epoch;
+    p.epoch_ptr = c->device_epoch ? c->epoch_word : nullptr;
     p.rows_per_flag = Ms / cps;
     p.n_flags = c->n_signals;
     p.wait_ticks = wait_ticks(c);
@@ -486,6 +511,7 @@ static int reduce_impl(agg_ctx* c, int Ms, int N, const float* const* slots, voi
         a.chunk_vec4 = (long long)(Ms / a.chunks) * N / 4;
     }
     a.epoch = c->epoch;
+    a.epoch_ptr = c->device_epoch ? c->epoch_word : nullptr;
     a.wait_ticks = wait_ticks(c);
     a.err = c->err;
     int nwg = n_workgroups;
@@ -541,7 +567,7 @@ int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb
                 // that the chip's clocks have settled under load before anything is compared
                 const int warm = res.configs_tried == 0 ? 30 : 1;
                 for (int it = 0; it < runs_per_config + warm && rc == AGG_OK; ++it) {
-                    if ((rc = signal_reset(c, nullptr)) != AGG_OK) break;
+                    if ((rc = signal_reset(c, c->consumer_stream)) != AGG_OK) break;   // ahead of the fork below
                     // fork: both streams start from the same point
                     if ((rc = hip_fail(hipEventRecord(e0, c->consumer_stream))) != AGG_OK) break;
                     if ((rc = hip_fail(hipStreamWaitEvent(c->producer_stream, e0, 0))) != AGG_OK) break;
@@ -624,6 +650,7 @@ int gemm_rs_scatter(agg_ctx* c, int M, int N, int Kl, const void* A_local, int l
     p.c_is_f32 = 1;
     p.c_vec_ok = N % 4 == 0;              // every destination is 16-byte aligned (checked above)
     p.epoch = c->epoch;
+    p.epoch_ptr = c->device_epoch ? c->epoch_word : nullptr;
     p.err = c->err;
     p.wait_ticks = wait_ticks(c);
     p.n_slices = W;
@@ -689,6 +716,7 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
         p.c_is_f32 = 1;
         p.c_vec_ok = N % 4 == 0;
         p.epoch = c->epoch;
+        p.epoch_ptr = c->device_epoch ? c->epoch_word : nullptr;
         p.err = c->err;
         p.wait_ticks = wait_ticks(c);
         p.n_slices = 1;
@@ -714,7 +742,7 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
     // workgroup of the (persistent) GEMM has long been resident, and the reducer takes the later chunks' signals itself.
     if (gemm_stream != reduce_stream) {
         bool waited = false;
-        if (c->can_wait_value) {
+        if (c->can_wait_value && !c->device_epoch) {   // (a stream wait compares with a value fixed at enqueue time)
             const int n_wait = (c->rs_own_last && P_other) ? 1 : c->rs_chunks;
             waited = true;
             for (int ch = 0; waited && ch < n_wait; ++ch)
@@ -817,6 +845,7 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     p.tiles_n = tiles_n;
     p.flags = gathered ? c->signals : nullptr;
     p.epoch = c->epoch;
+    p.epoch_ptr = c->device_epoch ? c->epoch_word : nullptr;
     p.n_flags = c->n_signals;
     p.rows_per_flag = r.rows_per_flag;
     p.wait_ticks = wait_ticks(c);
@@ -890,11 +919,12 @@ int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, 
     // 3. notify: the own slot is complete; then the reducer, which waits for the peers' signals itself
     int32_t* own_flag = c->signals + (size_t)c->rank * (c->n_signals / W) * kSignalStride;
     for (int ch = 0; ch < c->rs_chunks; ++ch)   // the reduction above completes all row chunks of the slot at once
-        if ((rc = hip_fail(launch_signal_set(own_flag + ch * kSignalStride, c->epoch, (hipStream_t)gemm_stream))) != AGG_OK)
+        if ((rc = hip_fail(launch_signal_set(own_flag + ch * kSignalStride, c->epoch, c->device_epoch ? c->epoch_word : nullptr,
+                                             (hipStream_t)gemm_stream))) != AGG_OK)
             return rc;
     if (gemm_stream != reduce_stream) {
         bool waited = false;
-        if (c->can_wait_value) {
+        if (c->can_wait_value && !c->device_epoch) {   // (a stream wait compares with a value fixed at enqueue time)
             // with a chunked own slot: every chunk's signal, one after the other
             waited = true;
             for (int ch = 0; waited && ch < c->rs_chunks; ++ch)

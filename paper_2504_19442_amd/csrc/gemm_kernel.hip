@@ -168,6 +168,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
         fr_off[h] = (lane & 31) * ROW_BYTES + (((2 * h + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
 
     const int KS = p.K / BK;             // stages
+    // the epoch the signals are compared with: the host's value at launch, or (for launches recorded in a HIP graph)
+    // the context's device word as it stands when the kernel starts
+    const int epoch = p.epoch_ptr ? __hip_atomic_load(p.epoch_ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : p.epoch;
     const int total_tiles = GROUPED ? *p.n_tiles_dev : p.tiles_m * p.tiles_n;
     const int G = gridDim.x;
     const int g = blockIdx.x;
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
             for (int f = f_lo + tid; f <= f_hi; f += 256) {
                 const int* fp = p.flags + (long long)f * kSignalStride;
                 const long long t0 = wall_clock64();
-                while (__hip_atomic_load(fp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.epoch) {
+                while (__hip_atomic_load(fp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
                     if (__hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
                         wall_clock64() - t0 > p.wait_ticks) {
                         gave_up = 1;
@@ -593,7 +596,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                             const int prev = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
                             if (prev == target - 1) {
                                 __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                __hip_atomic_store(p.slice_flag[w] + c * kSignalStride, p.epoch, __ATOMIC_RELEASE,
+                                __hip_atomic_store(p.slice_flag[w] + c * kSignalStride, epoch, __ATOMIC_RELEASE,
                                                    __HIP_MEMORY_SCOPE_AGENT);
                             }
                         }

@@ -25,6 +25,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
 {
     const int tid = threadIdx.x;
+    const int epoch = a.epoch_ptr ? __hip_atomic_load(a.epoch_ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.epoch;
     const int team = a.team;
     const int n_teams = gridDim.x / team;
     const int t = blockIdx.x / team, j = blockIdx.x - t * team;
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
             const int prev = __hip_atomic_fetch_add(a.counters + f, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (prev == team - 1) {
                 __hip_atomic_store(a.counters + f, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.flags + (long long)f * kSignalStride, a.epoch, __ATOMIC_RELAXED,
+                __hip_atomic_store(a.flags + (long long)f * kSignalStride, epoch, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -82,6 +83,7 @@ __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
 __global__ __launch_bounds__(256) void producer_links_kernel(const ProducerArgs a)
 {
     const int tid = threadIdx.x;
+    const int epoch = a.epoch_ptr ? __hip_atomic_load(a.epoch_ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.epoch;
     const int link = blockIdx.x % a.n_jobs, j = blockIdx.x / a.n_jobs;
     if (j >= a.link_wgs) return;
     const long long t0 = wall_clock64();
@@ -124,16 +126,25 @@ __global__ __launch_bounds__(256) void producer_links_kernel(const ProducerArgs 
             const int prev = __hip_atomic_fetch_add(a.counters + f, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (prev == a.link_wgs - 1) {
                 __hip_atomic_store(a.counters + f, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.flags + (long long)f * kSignalStride, a.epoch, __ATOMIC_RELAXED,
+                __hip_atomic_store(a.flags + (long long)f * kSignalStride, epoch, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
 }
 
-__global__ void signal_set_kernel(int* flag, int value)
+// value_ptr not null: the value is read from that device word (the context's epoch word) when the kernel runs
+__global__ void signal_set_kernel(int* flag, int value, const int* value_ptr)
 {
+    if (value_ptr) value = __hip_atomic_load(value_ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// signal_reset with the epoch kept on the device: one thread, ordered by its stream like any other kernel
+__global__ void epoch_advance_kernel(int* epoch_word)
+{
+    const int e = __hip_atomic_load(epoch_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(epoch_word, e + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 hipError_t launch_producer(const ProducerArgs& a_in, int n_workgroups, hipStream_t stream)
@@ -182,9 +193,15 @@ hipError_t launch_signal_probe(const int* flag, int value, long long ticks, int*
     return hipGetLastError();
 }
 
-hipError_t launch_signal_set(int* flag, int value, hipStream_t stream)
+hipError_t launch_signal_set(int* flag, int value, const int* value_ptr, hipStream_t stream)
 {
-    hipLaunchKernelGGL(signal_set_kernel, dim3(1), dim3(1), 0, stream, flag, value);
+    hipLaunchKernelGGL(signal_set_kernel, dim3(1), dim3(1), 0, stream, flag, value, value_ptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_epoch_advance(int* epoch_word, hipStream_t stream)
+{
+    hipLaunchKernelGGL(epoch_advance_kernel, dim3(1), dim3(1), 0, stream, epoch_word);
     return hipGetLastError();
 }
 

@@ -51,6 +51,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
 {
     const int tid = threadIdx.x;
     const int W = WT > 0 ? WT : a.W;
+    const int epoch = a.epoch_ptr ? __hip_atomic_load(a.epoch_ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.epoch;
     const long long stride = (long long)gridDim.x * 256;
     int seen = 0;                      // slots 0..seen-1 are known to have arrived (uniform over the workgroup)
     int chunks_seen = 0;               // chunked slots: row chunks 0..chunks_seen-1 of EVERY slot have arrived
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
                 if (tid == 0) {
                     for (int c = chunks_seen; ok && c <= need; ++c)
                         for (int w = 0; ok && w < W; ++w)
-                            ok = wait_signal(a.flags + ((long long)w * a.flag_step + c) * kSignalStride, a.epoch,
+                            ok = wait_signal(a.flags + ((long long)w * a.flag_step + c) * kSignalStride, epoch,
                                              a.wait_ticks, a.err);
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                 }
@@ -85,10 +86,10 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
                 if (w >= seen) {
                     int ok = 1, upto = w + 1;
                     if (tid == 0) {
-                        ok = wait_signal(a.flags + (long long)w * a.flag_step * kSignalStride, a.epoch, a.wait_ticks, a.err);
+                        ok = wait_signal(a.flags + (long long)w * a.flag_step * kSignalStride, epoch, a.wait_ticks, a.err);
                         while (ok && upto < W &&
                                __hip_atomic_load(a.flags + (long long)upto * a.flag_step * kSignalStride, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT) >= a.epoch)
+                                                 __HIP_MEMORY_SCOPE_AGENT) >= epoch)
                             ++upto;
                         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                     }
