@@ -18,7 +18,7 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
 {
     const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     extern __shared__ int hist[];                 // [E] counts
-    __shared__ int wave_cnt[4][4];
+    __shared__ int wave_cnt[2][8][4];
     __shared__ int s_seg_lo, s_first;
     for (int i = tid; i < a.E; i += 256) hist[i] = 0;
     __syncthreads();
@@ -60,49 +60,63 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
     }
     if (tid == 0) a.seg_off[e] = seg_lo;
 
-    // ---- pass 2: stable placement, 1024 pairs per step (lane handles 4 consecutive pairs)
+    // ---- pass 2: stable placement, 1024 pairs per step (lane handles 4 consecutive pairs), U steps per pass of the
+    // loop: their ids are loaded together and their counts exchanged with one barrier, not one per step.
+    constexpr int U = 8;
     int running = seg_lo;
-    for (int base = 0; base < a.P; base += 1024) {
-        const int i0 = base + 4 * tid;
-        int v[4];
+    for (int base0 = 0; base0 < a.P; base0 += 1024 * U) {
+      int vv[U][4];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i0 = base0 + u * 1024 + 4 * tid;
         if (i0 + 3 < a.P && (a.P & 3) == 0) {
             const int4 q = ids4[i0 >> 2];
-            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+            vv[u][0] = q.x; vv[u][1] = q.y; vv[u][2] = q.z; vv[u][3] = q.w;
         } else {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = i0 + k < a.P ? a.topk_ids[i0 + k] : -1;
+            for (int k = 0; k < 4; ++k) vv[u][k] = i0 + k < a.P ? a.topk_ids[i0 + k] : -1;
         }
-        int mine = 0;
+      }
+      // counts of this expert's pairs: per lane, then per wave, for all U steps; one barrier; then the positions
+      int mine[U], incl[U];
+      const int par = (base0 / (1024 * U)) & 1;       // wave_cnt is double-buffered over the passes of this loop
 #pragma unroll
-        for (int k = 0; k < 4; ++k) mine += (v[k] == e);
-        // exclusive prefix of `mine` over the workgroup, in thread order
-        int incl = mine;
+      for (int u = 0; u < U; ++u) {
+        mine[u] = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) mine[u] += (vv[u][k] == e);
+        // inclusive prefix of `mine` over the wave, in lane order
+        incl[u] = mine[u];
 #pragma unroll
         for (int sft = 1; sft < 64; sft <<= 1) {
-            const int t = __shfl_up(incl, sft);
-            if (lane >= sft) incl += t;
+            const int t = __shfl_up(incl[u], sft);
+            if (lane >= sft) incl[u] += t;
         }
-        if (lane == 63) wave_cnt[(base >> 10) & 3][wave] = incl;
-        __syncthreads();
+        if (lane == 63) wave_cnt[par][u][wave] = incl[u];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i0 = base0 + u * 1024 + 4 * tid;
         int before = 0, total = 0;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const int c = wave_cnt[(base >> 10) & 3][w];
+            const int c = wave_cnt[par][u][w];
             if (w < wave) before += c;
             total += c;
         }
-        int pos = running + before + incl - mine;
+        int pos = running + before + incl[u] - mine[u];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            if (v[k] == e) {
+            if (vv[u][k] == e) {
                 if (a.pair_pos) a.pair_pos[i0 + k] = pos;
                 a.sorted_token[pos++] = (i0 + k) / a.topk;
-            } else if (e == 0 && a.pair_pos && i0 + k < a.P && (unsigned)v[k] >= (unsigned)a.E) {
+            } else if (e == 0 && a.pair_pos && i0 + k < a.P && (unsigned)vv[u][k] >= (unsigned)a.E) {
                 a.pair_pos[i0 + k] = -1;          // an id outside [0, E): the pair is nowhere in the sorted order
             }
         }
         running += total;
-        // wave_cnt is used round-robin over four steps, so one barrier per step is enough
+      }
     }
     // ---- tile entries (they read sorted_token written above by this same workgroup)
     __threadfence_block();
