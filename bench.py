@@ -100,6 +100,9 @@ def main() -> int:
     ap.add_argument("--shape", default="", help="profiling aid: W,Ms,K,N of an ad-hoc AllGather-GEMM shape")
     ap.add_argument("--only-gemm", action="store_true",
                     help="profiling aid: deliver the shards once, then time the GEMM alone (prints a short line)")
+    ap.add_argument("--only-reducer", action="store_true",
+                    help="profiling aid: the ReduceScatter reducer alone at its full size (prints a short line); with "
+                         "--pmc-calibration a 256 MiB copy of known size runs first")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (peers are emulated on the same GPU); use --gpus 1",
@@ -112,6 +115,37 @@ def main() -> int:
     import paper_2504_19442_amd as agg
     import workloads as wl
     from gpu_util import AgGemmRun
+
+    if args.only_reducer:
+        rs = wl.RS_FULL
+        if args.pmc_calibration:
+            src = torch.ones(256 << 20, device="cuda", dtype=torch.uint8)
+            dst = torch.empty_like(src)
+            dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        slots = [torch.randn((rs.Ms, rs.N), device="cuda", dtype=torch.float32) for _ in range(rs.W)]
+        R = torch.empty((rs.Ms, rs.N), device="cuda", dtype=torch.float32)
+        rctx = agg.symm_alloc(rs.W, 0, 16, rs.W)
+        _, rc_ = rctx.streams()
+        agg.signal_reset(rctx)
+        for w in range(rs.W):
+            agg.signal_set(rctx, w, rc_)
+        for _ in range(args.warmup):
+            agg.rs_reduce(rctx, rs.Ms, rs.N, slots, R, rs.N, agg.F32, 0, rc_)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            agg.rs_reduce(rctx, rs.Ms, rs.N, slots, R, rs.N, agg.F32, 0, rc_)
+        torch.cuda.synchronize()
+        t = (time.perf_counter() - t0) / args.steps
+        assert agg.agg_status(rctx) == agg.OK
+        rctx.free()
+        print(json.dumps({"only_reducer_ms": round(t * 1e3, 4), "bytes": rs.reducer_bytes,
+                          "achieved_GBps": round(rs.reducer_bytes / t / 1e9, 1),
+                          "frac_of_hbm_peak": round(rs.reducer_bytes / t / 1e9 / PEAK_HBM_GBPS, 4),
+                          "workload": rs.name}), flush=True)
+        return 0
 
     if args.shape:
         W_, Ms_, K_, N_ = (int(x) for x in args.shape.split(","))
