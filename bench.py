@@ -20,10 +20,10 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak (published)
 
 
-def _measured_traffic(workload: str):
-    """HBM bytes per GEMM launch measured with rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy of
+def _measured_traffic(workload: str, summary: str = "gemm_kernel_{}_hbm_traffic.txt"):
+    """HBM bytes per kernel launch measured with rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy of
     known size); read from the committed summary of that measurement, None if there is none for this workload."""
-    path = os.path.join(ROOT, "profiles", f"gemm_kernel_{workload}_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", summary.format(workload))
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -422,6 +422,7 @@ def main() -> int:
         assert agg.agg_status(rctx) == agg.OK
         rctx.free()
         out["reducer"] = {"workload": rs.name, "bytes": rs.reducer_bytes, "ms": round(t_red * 1e3, 4),
+                          "traffic": _measured_traffic(rs.name, "reduce_kernel_{}.txt"),
                           "achieved_GBps": round(rs.reducer_bytes / t_red / 1e9, 1),
                           "frac_of_hbm_peak": round(rs.reducer_bytes / t_red / 1e9 / PEAK_HBM_GBPS, 4)}
 
