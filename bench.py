@@ -103,6 +103,9 @@ def main() -> int:
     ap.add_argument("--only-reducer", action="store_true",
                     help="profiling aid: the ReduceScatter reducer alone at its full size (prints a short line); with "
                          "--pmc-calibration a 256 MiB copy of known size runs first")
+    ap.add_argument("--only-moe", action="store_true",
+                    help="profiling aid: routing + grouped GEMM of the MoE shape alone, tokens already gathered "
+                         "(prints a short line); --pmc-calibration as for --only-reducer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (peers are emulated on the same GPU); use --gpus 1",
@@ -116,14 +119,52 @@ def main() -> int:
     import workloads as wl
     from gpu_util import AgGemmRun
 
+    if (args.only_reducer or args.only_moe) and args.pmc_calibration:
+        src = torch.ones(256 << 20, device="cuda", dtype=torch.uint8)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    if args.only_moe:
+        ms = wl.MOE_FULL
+        gen = torch.Generator(device="cuda").manual_seed(4000)
+        Xs = [(torch.rand((ms.tokens_per_rank, ms.K), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
+              for _ in range(ms.W)]
+        Wt = (torch.randn((ms.E, ms.N, ms.K), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+        ids = torch.rand((ms.T, ms.E), device="cuda", generator=gen).argsort(dim=1)[:, : ms.topk].to(torch.int32).contiguous()
+        mctx = agg.symm_alloc(ms.W, 0, ms.tokens_per_rank * ms.K * 2, ms.W * args.chunks)
+        mp, mc = mctx.streams()
+        mctx.set_tile_config(args.tile)
+        Pm = ms.T * ms.topk
+        Ym = torch.empty((Pm, ms.N), device="cuda", dtype=torch.bfloat16)
+        tok = torch.empty((Pm,), device="cuda", dtype=torch.int32)
+        seg = torch.empty((ms.E + 1,), device="cuda", dtype=torch.int32)
+        agg.signal_reset(mctx)
+        agg.ag_producer_emulate(mctx, Xs, None, agg.PRODUCER_KERNEL, 0, mp)
+        torch.cuda.synchronize()
+
+        def step_moe_only():
+            agg.ag_moe_gemm(mctx, ms.T, ms.topk, ms.E, ms.N, ms.K, ids, Wt, tok, seg, Ym, ms.N, agg.BF16, mc)
+
+        for _ in range(args.warmup):
+            step_moe_only()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_moe_only()
+        torch.cuda.synchronize()
+        t = (time.perf_counter() - t0) / args.steps
+        assert agg.agg_status(mctx) == agg.OK
+        mctx.free()
+        moe_bytes = Wt.numel() * 2 + ms.T * ms.K * 2 + Pm * ms.N * 2
+        print(json.dumps({"only_moe_ms": round(t * 1e3, 4), "tflops": round(ms.flops / t / 1e12, 1),
+                          "algorithmic_bytes": moe_bytes, "algorithmic_GBps": round(moe_bytes / t / 1e9, 1),
+                          "workload": ms.name, "tile_config": args.tile}), flush=True)
+        return 0
+
     if args.only_reducer:
         rs = wl.RS_FULL
-        if args.pmc_calibration:
-            src = torch.ones(256 << 20, device="cuda", dtype=torch.uint8)
-            dst = torch.empty_like(src)
-            dst.copy_(src)
-            torch.cuda.synchronize()
-            del src, dst
         slots = [torch.randn((rs.Ms, rs.N), device="cuda", dtype=torch.float32) for _ in range(rs.W)]
         R = torch.empty((rs.Ms, rs.N), device="cuda", dtype=torch.float32)
         rctx = agg.symm_alloc(rs.W, 0, 16, rs.W)
