@@ -192,7 +192,7 @@ int gemm_rs(agg_ctx* ctx, int M, int N, int Klocal,
 /*
  * Tuning (Section 3.8, the autotuner for overlapped kernels).  What is timed is the whole overlapped function:
  * signal_reset, ag_producer_emulate (rotated arrival order) on the context's producer stream, ag_gemm on its consumer
- * stream, join -- with the signals reset before every run, never a kernel repeated on its own.  Candidates: the three
+ * stream, join -- with the signals reset before every run, never a kernel repeated on its own.  Candidates: the four
  * tile shapes x both tile orders x three producer sizes (half, one and two workgroups per compute unit; one candidate
  * when the copy engines are used).  Each candidate runs once to warm up (the very first thirty times, so that the
  * chip's clocks have settled) and runs_per_config more times; the median run counts.  The best configuration is stored in the context (tile shape, tile order, producer
@@ -336,7 +336,7 @@ int moe_rs(agg_ctx* ctx, int Ttok, int topk, int E, int N, int Klocal,
            const float* const* slots, float* Z_other, void* R, int ldr, int r_dtype,
            void* gemm_stream, void* reduce_stream);
 
-/* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default; never 3), 0 = 256x224, 1 = 128x128,
+/* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 128x128,
  * 2 = 256x256, 3 = 128x256.  A tuning knob (Section 3.8); every shape gives the same result (the sum over K runs in
  * the same order in all of them). */
 int agg_set_tile_config(agg_ctx* ctx, int tile_config);

@@ -36,11 +36,12 @@ inline long long wait_ticks(const agg_ctx* c)
 int choose_tile(const agg_ctx* c, int M, int N)
 {
     if (c->tile_config >= 0) return c->tile_config;
-    const int cand[3] = {TILE_256x224, TILE_256x256, TILE_128x128};
-    const double eff[3] = {1.0, 1.0, 0.75};
+    // measured rates per flop relative to the large shapes (70B shape, GEMM alone): 128x256 0.86, 128x128 0.78
+    const int cand[4] = {TILE_256x224, TILE_256x256, TILE_128x256, TILE_128x128};
+    const double eff[4] = {1.0, 1.0, 0.86, 0.75};
     int best = cand[0];
     double best_cost = 1e300;
-    for (int i = 0; i < 3; ++i) {
+    for (int i = 0; i < 4; ++i) {
         const TileShape t = tile_shape(cand[i]);
         const long long tiles = (long long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
         const long long waves = (tiles + c->num_cus - 1) / c->num_cus;
@@ -543,7 +544,7 @@ int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb
 {
     if (!c || !out || runs_per_config < 1 || runs_per_config > 1000) return AGG_ERR_INVALID_ARG;
     const int saved_tile = c->tile_config, saved_order = c->tile_order, saved_wgs = c->producer_wgs;
-    const int tiles[3] = {TILE_256x224, TILE_256x256, TILE_128x128};
+    const int tiles[4] = {TILE_256x224, TILE_256x256, TILE_128x256, TILE_128x128};
     const int orders[2] = {AGG_ORDER_ROTATED, AGG_ORDER_SUBCHUNK};
     const int wgs[3] = {c->num_cus / 2 > 0 ? c->num_cus / 2 : 1, c->num_cus, 2 * c->num_cus};
     hipEvent_t e0 = nullptr, e1 = nullptr, join = nullptr;
@@ -556,7 +557,7 @@ int agg_autotune_ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb
         (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return rc;
     }
     const bool sdma = (producer_mode & 0xff) == AGG_PRODUCER_SDMA;
-    for (int ti = 0; ti < 3 && rc == AGG_OK; ++ti)
+    for (int ti = 0; ti < 4 && rc == AGG_OK; ++ti)
         for (int oi = 0; oi < 2 && rc == AGG_OK; ++oi)
             for (int wi = 0; wi < (sdma ? 1 : 3) && rc == AGG_OK; ++wi) {
                 c->tile_config = tiles[ti];
