@@ -459,7 +459,7 @@ def main() -> int:
         def step_reduce():
             agg.rs_reduce(rctx, rs.Ms, rs.N, slots, R, rs.N, agg.F32, 0, rc_)
 
-        t_red = timed(step_reduce, 50, 5)
+        t_red = timed(step_reduce, 100, 100)
         assert agg.agg_status(rctx) == agg.OK
         rctx.free()
         out["reducer"] = {"workload": rs.name, "bytes": rs.reducer_bytes, "ms": round(t_red * 1e3, 4),
@@ -467,45 +467,52 @@ def main() -> int:
                           "achieved_GBps": round(rs.reducer_bytes / t_red / 1e9, 1),
                           "frac_of_hbm_peak": round(rs.reducer_bytes / t_red / 1e9 / PEAK_HBM_GBPS, 4)}
 
-        # GEMM + ReduceScatter at its full size: one GEMM launch (own slice first) with the reducer beside it;
-        # the peers' slots are signalled before the launch (values drawn on the device, same distributions)
+        # GEMM + ReduceScatter at its full size: one GEMM launch with the reducer on a second stream; the peers'
+        # slots are signalled before the launch (values drawn on the device, same distributions).  Four variants,
+        # alternated over three rounds after a common warm-up (the first thing timed after a pause runs slow).
         gen = torch.Generator(device="cuda").manual_seed(4000)
         A_loc = (torch.rand((rs.M, rs.Kl), device="cuda", generator=gen) * 2 - 1).to(torch.bfloat16)
         B_loc = (torch.randn((rs.N, rs.Kl), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
         P_other = torch.empty((rs.M, rs.N), device="cuda", dtype=torch.float32)
-        gctx = agg.symm_alloc(rs.W, 0, 16, rs.W)
+        RS_K = 4
+        gctx = agg.symm_alloc(rs.W, 0, 16, rs.W * RS_K)
         gp, gc = gctx.streams()
 
-        def step_gemm_rs():
-            agg.signal_reset(gctx)
-            for w in range(1, rs.W):          # the peers' slots "arrive" on the reduce stream, ahead of the reducer
-                agg.signal_set(gctx, w, gc)
-            agg.gemm_rs(gctx, rs.M, rs.N, rs.Kl, A_loc, rs.Kl, B_loc, rs.Kl, agg.B_NK, slots, P_other, R, rs.N,
-                        agg.F32, gp, gc)
+        def step_gemm_rs(own_last, chunks):
+            def f():
+                gctx.set_rs_own_slice_last(own_last)
+                gctx.set_rs_chunks(chunks)
+                agg.signal_reset(gctx)
+                for w in range(1, rs.W):      # the peers' slots "arrive" on the reduce stream, ahead of the reducer
+                    for c_ in range(chunks):
+                        agg.signal_set(gctx, w * RS_K + c_, gc)
+                agg.gemm_rs(gctx, rs.M, rs.N, rs.Kl, A_loc, rs.Kl, B_loc, rs.Kl, agg.B_NK, slots, P_other, R, rs.N,
+                            agg.F32, gp, gc)
+            return f
 
-        t_grs = timed(step_gemm_rs, 20, 3)
+        def step_gemm_rs_gemm_only():        # the GEMM half alone: own slice into its slot, the rest into P_other
+            agg.gemm_rs_scatter(gctx, rs.M, rs.N, rs.Kl, A_loc, rs.Kl, B_loc, rs.Kl, agg.B_NK,
+                                [slots[0]] + [None] * (rs.W - 1), P_other, None, 0, gp)
+
+        variants = {"default": step_gemm_rs(True, 1), "last4": step_gemm_rs(True, RS_K),
+                    "first": step_gemm_rs(False, 1), "gemm": step_gemm_rs_gemm_only}
+        timed(variants["default"], 100, 0)
+        grs = {k: [] for k in variants}
+        for _ in range(3):
+            for k, fn in variants.items():
+                grs[k].append(timed(fn, 20, 3))
         assert agg.agg_status(gctx) == agg.OK
-        # the schedule of a node: own slice last, its four row chunks signalled one by one to the reducer
         gctx.free()
-        gctx = agg.symm_alloc(rs.W, 0, 16, rs.W * 4)
-        gp, gc = gctx.streams()
-        gctx.set_rs_chunks(4)
-        gctx.set_rs_own_slice_last(True)
-
-        def step_gemm_rs_own_last():
-            agg.signal_reset(gctx)
-            for s in range(4, rs.W * 4):
-                agg.signal_set(gctx, s, gc)
-            agg.gemm_rs(gctx, rs.M, rs.N, rs.Kl, A_loc, rs.Kl, B_loc, rs.Kl, agg.B_NK, slots, P_other, R, rs.N,
-                        agg.F32, gp, gc)
-
-        t_grs_last = timed(step_gemm_rs_own_last, 20, 3)
-        assert agg.agg_status(gctx) == agg.OK
-        gctx.free()
+        t_grs, t_grs_last, t_grs_first, t_grs_gemm = (float(np.median(grs[k])) for k in ("default", "last4", "first", "gemm"))
         out["gemm_rs"] = {"workload": rs.name, "ms": round(t_grs * 1e3, 4),
                           "ms_own_slice_last_4_chunks": round(t_grs_last * 1e3, 4),
+                          "ms_own_slice_first": round(t_grs_first * 1e3, 4),
+                          "ms_gemm_alone": round(t_grs_gemm * 1e3, 4),
+                          "gemm_alone_tflops": round(2.0 * rs.M * rs.N * rs.Kl / t_grs_gemm / 1e12, 1),
                           "gemm_tflops": round(2.0 * rs.M * rs.N * rs.Kl / t_grs / 1e12, 1),
-                          "note": "GEMM (fp32 out, 8192x8192x3584) + reducer on a second stream, per step"}
+                          "protocol": "medians of 3 alternating rounds of 20 steps after 100 warm-up steps",
+                          "note": "GEMM (fp32 out, 8192x8192x3584) + reducer on a second stream, per step; "
+                                  "ms = the library's default (own slice last, one signal per slice)"}
         del A_loc, B_loc, P_other, slots, R
 
         # MoE AllGather grouped GEMM at the Table 4 shape: routing + gated grouped GEMM, producer beside it
@@ -532,7 +539,7 @@ def main() -> int:
             agg.ag_moe_gemm(mctx, ms.T, ms.topk, ms.E, ms.N, ms.K, ids, Wt, tok, seg, Ym, ms.N, agg.BF16, mc)
             hev.record(ev_m, mc)
 
-        t_moe = timed(step_moe, 20, 3)
+        t_moe = timed(step_moe, 30, 60)
         assert agg.agg_status(mctx) == agg.OK
         mctx.free()
         moe_bytes = Wt.numel() * 2 + ms.T * ms.K * 2 + Pm * ms.N * 2
@@ -565,7 +572,7 @@ def main() -> int:
             agg.moe_rs(qctx, mr.T, mr.topk, mr.E, mr.N, mr.Kl, Hh, W2, ids2, g2, Yw, tk2, sg2, pp2, sl2, None, R2, mr.N,
                        agg.F32, qp, qc)
 
-        t_mrs = timed(step_moe_rs, 20, 3)
+        t_mrs = timed(step_moe_rs, 50, 100)
         assert agg.agg_status(qctx) == agg.OK
         qctx.free()
         # bytes that have to move: H and the weights once, Y written and read once, the slots read, R written

@@ -176,8 +176,9 @@ int rs_reduce(agg_ctx* ctx, int Ms, int N, const float* const* slots,
 /*
  * GEMM + ReduceScatter for one rank (Section 3.3, Algorithm 3; Section 4.1 "GEMM ReduceScatter").
  * Enqueues on gemm_stream the local partial product P[M, N] = A_local[M, Klocal] . B_local (bf16 in, fp32
- * out, un-gated), computing this rank's row slice [rank*Ms, (rank+1)*Ms) first and writing it straight
- * into slots[rank]; when that slice is complete its signal is set (the producer signal of Algorithm 3).
+ * out, un-gated), writing this rank's row slice [rank*Ms, (rank+1)*Ms) straight into slots[rank] (it is computed
+ * last by default, first with agg_set_rs_own_slice_last(ctx, 0)); when that slice is complete its signal is set
+ * (the producer signal of Algorithm 3).
  * The other rows go to P_other (fp32 [M, N], leading dimension N; rows of the own slice are not written;
  * may be NULL to skip computing them).  Enqueues on reduce_stream a stream-level wait for the own slot's
  * signal (it holds no compute unit, so the GEMM can always become resident) and then the reduction of
@@ -304,10 +305,10 @@ int agg_set_rs_chunks(agg_ctx* ctx, int chunks);
 
 /*
  * Order of the slices inside gemm_rs (Section 3.7: a rank computes the slices that have to travel first and keeps its
- * own for last).  0 (default): the own slice first -- on one GPU the peers' slots are there early, so the reducer can
- * run beside the whole rest of the GEMM.  1: the own slice last, as on a node; the reducer then starts when the first
- * chunk of the own slice (agg_set_rs_chunks) is complete and reduces chunk by chunk behind the GEMM.  The results are
- * the same bit for bit.
+ * own for last).  1 (default): the own slice last, as on a node; the reducer starts when the first chunk of the own
+ * slice (agg_set_rs_chunks) is complete and reduces chunk by chunk behind the end of the GEMM.  0: the own slice
+ * first, so that the reducer runs beside the whole rest of the GEMM (measured equally fast on one GPU, where the
+ * peers' slots do not have to travel).  The results are the same bit for bit.
  */
 int agg_set_rs_own_slice_last(agg_ctx* ctx, int on);
 

@@ -161,6 +161,7 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     c->wait_limit_us = 2000000;
     c->tile_config = -1;
     c->rs_chunks = 1;
+    c->rs_own_last = 1;
     int rc = AGG_OK;
     hipDeviceProp_t prop;
     int khz = 0;
