@@ -313,13 +313,13 @@ def main() -> int:
         acc = {"fused": [], "gemm": [], "copy": [], "serial": []}
         for _ in range(rounds):
             hev.record(ev_cons_done, cons_h)
-            acc["fused"].append(timed(step_fused_plain, n2, 2))
+            acc["fused"].append(timed(step_fused_plain, n2, 10))
             agg.signal_reset(ctx)
             step_copy()
             torch.cuda.synchronize()            # signals of this epoch are set: the GEMM alone does not wait
-            acc["gemm"].append(timed(step_gemm, n2, 2))
-            acc["copy"].append(timed(step_copy, n2, 2))
-            acc["serial"].append(timed(step_serial, n2, 2))
+            acc["gemm"].append(timed(step_gemm, n2, 10))
+            acc["copy"].append(timed(step_copy, n2, 10))
+            acc["serial"].append(timed(step_serial, n2, 10))
         assert agg.agg_status(ctx) == agg.OK
         t_fused2, t_gemm, t_copy, t_serial = (float(np.median(acc[k])) for k in ("fused", "gemm", "copy", "serial"))
         out["overlap"] = {
@@ -377,11 +377,11 @@ def main() -> int:
         for _ in range(3):
             hev.record(ev_cons_done, cons_h)
             ctx.set_tile_order(agg.ORDER_SUBCHUNK)
-            mesh["sub"].append(timed(step_mesh, n3, 2))
+            mesh["sub"].append(timed(step_mesh, n3, 10))
             ctx.set_tile_order(agg.ORDER_ROTATED)
-            mesh["rot"].append(timed(step_mesh, n3, 2))
-            mesh["copy"].append(timed(step_mesh_copy, n3, 2))
-            mesh["serial"].append(timed(step_mesh_serial, n3, 2))
+            mesh["rot"].append(timed(step_mesh, n3, 10))
+            mesh["copy"].append(timed(step_mesh_copy, n3, 10))
+            mesh["serial"].append(timed(step_mesh_serial, n3, 10))
         assert agg.agg_status(ctx) == agg.OK
         ctx.set_link_rate(0.0)
         m_sub, m_rot, m_copy, m_serial = (float(np.median(mesh[k])) for k in ("sub", "rot", "copy", "serial"))
