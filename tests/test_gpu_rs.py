@@ -411,6 +411,26 @@ def test_reducer_with_chunk_signals_times_out_on_a_missing_chunk():
         run.close()
 
 
+def test_all_ranks_seeded_random_shapes_and_chunkings():
+    # world size, chunk count, rows per chunk (smaller and larger than a tile, not powers of two), width and tile
+    # shape drawn from a seeded generator: chunk counters and signals of every (slice, chunk) must come out right
+    rng = np.random.default_rng(77)
+    done = 0
+    while done < 14:
+        W = int(rng.choice([1, 2, 3, 4, 5, 8]))
+        k = int(rng.choice([1, 2, 3, 5, 8, 16]))
+        rows_per_chunk = int(rng.choice([1, 2, 6, 8, 32, 40, 64, 128]))
+        Ms = k * rows_per_chunk
+        N = int(rng.choice([4, 36, 100, 224, 260, 512]))
+        if W * Ms > 2048 or (rows_per_chunk * N) % 4:
+            continue
+        Kl = 64 * int(rng.integers(1, 4))
+        tile = int(rng.choice([-1, 0, 1, 2, 3]))
+        sh = wl.GemmRsShape(f"rs_random_{done}", 60 + done, W, W * Ms, Kl, N)
+        _all_ranks_gemm_rs(sh, reducers_first=False, tile=None if tile < 0 else tile, chunks=k)
+        done += 1
+
+
 @pytest.mark.parametrize("chunks", [1, 2])
 def test_all_ranks_pull_mode(chunks):
     # Pull mode (Section 3.5 names both): every rank keeps its whole partial product P_w at home and only notifies;
