@@ -1,4 +1,5 @@
-"""Helpers for the GPU parity tests: device buffers (torch is used for memory and streams only)."""
+"""Device-side harness shared by the GPU tests, bench.py and the smoke run: device buffers for the seeded inputs and
+one AllGather-GEMM problem set up on a context (torch is used for memory and streams only; no arithmetic of the method)."""
 import numpy as np
 import torch
 

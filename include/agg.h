@@ -76,8 +76,8 @@ int32_t* symm_signals(agg_ctx* ctx);         /* device pointer to S (signal i at
 int symm_epoch(agg_ctx* ctx);                /* current epoch (host value) */
 
 /*
- * Two streams the context owns, for the communication part and the computation part (Section 2.3: the host
- * "launches the communication part and the computation part on different streams").  Kernels of streams that
+ * Two streams the context owns, for the communication part and the computation part (Section 2.3: the host puts
+ * communication and computation on separate streams).  Kernels of streams that
  * share a hardware queue run one after the other, and a consumer launched ahead of its producer on such a pair
  * would wait for signals that cannot come (its waits are bounded, so it would time out, not hang).  Which queue
  * a stream gets cannot be chosen, so symm_alloc tries it out: it keeps the first of up to eight new streams on
@@ -87,7 +87,7 @@ int symm_epoch(agg_ctx* ctx);                /* current epoch (host value) */
 int symm_streams(agg_ctx* ctx, void** producer_stream, void** consumer_stream);
 
 /*
- * "Reset all the signals" before every run of an overlapped function (Section 3.8, the autotuner's rule).
+ * Every signal is reset before every run of an overlapped function (Section 3.8, the autotuner's rule).
  * Advances the epoch; calls issued afterwards wait for, and set, the new epoch.  The caller orders the
  * previous run's kernels before the next run's producer (they share T).  `stream` is used only with
  * agg_set_device_epoch(ctx, 1).

@@ -339,7 +339,7 @@ done:
     return rc;
 }
 
-/* -------------------------------------------------- Section 3.5 sizing bound */
+/* -------------------------------------------------- MoE + ReduceScatter (Section 4.1) */
 
 /*
  * MoE + ReduceScatter for one rank (Section 4.1, "MoE ReduceScatter": grouped GEMM, top-k reduction, reduce

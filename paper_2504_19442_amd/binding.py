@@ -38,8 +38,8 @@ EXPORTS = [
 
 
 def lib_path() -> str:
-    """The built library; AGG_LIB_PATH names another build of the same sources (kernel experiments)."""
-    return os.environ.get("AGG_LIB_PATH") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libagg.so")
+    """The built library, beside this file."""
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libagg.so")
 
 
 _LIB = None

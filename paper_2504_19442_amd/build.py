@@ -21,12 +21,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-i
          "-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"]
 
 
-def check_agprs(extra_flags=(), allow_scratch=False) -> None:
+def check_agprs() -> None:
     """Compile the GEMM kernel to assembly and fail if the compiler itself touches an accumulator register
     (any a<N> outside the inline-asm blocks), or if a kernel spills to scratch."""
     import re
     src = os.path.join(CSRC, "gemm_kernel.hip")
-    r = subprocess.run([HIPCC, *FLAGS, *extra_flags, "--cuda-device-only", "-S", src, "-o", "-"],
+    r = subprocess.run([HIPCC, *FLAGS, "--cuda-device-only", "-S", src, "-o", "-"],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(r.stderr)
@@ -42,7 +42,7 @@ def check_agprs(extra_flags=(), allow_scratch=False) -> None:
             code = t.split(";")[0]
             if pat.search(code):
                 raise RuntimeError(f"compiler-allocated accumulator register in gemm_kernel (asm line {n}): {t}")
-        if t.startswith("; ScratchSize:") and t.split(":")[1].strip() != "0" and not allow_scratch:
+        if t.startswith("; ScratchSize:") and t.split(":")[1].strip() != "0":
             raise RuntimeError(f"gemm_kernel spills to scratch: {t}")
 
 
@@ -59,23 +59,6 @@ def _compile(src: str) -> str:
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj
-
-
-def build_variant(out_path: str, extra_flags: list) -> str:
-    """Build the same sources with extra compiler flags into out_path (kernel experiments; never the product)."""
-    import tempfile
-    check_agprs(extra_flags, allow_scratch=True)
-    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-    with tempfile.TemporaryDirectory() as tmp:
-        objs = []
-        for src in srcs:
-            obj = os.path.join(tmp, os.path.basename(src) + ".o")
-            r = subprocess.run([HIPCC, *FLAGS, *extra_flags, "-c", src, "-o", obj], capture_output=True, text=True)
-            if r.returncode != 0:
-                raise RuntimeError(r.stderr)
-            objs.append(obj)
-        subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out_path], check=True)
-    return out_path
 
 
 def build(force: bool = True) -> str:

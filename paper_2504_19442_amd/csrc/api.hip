@@ -175,9 +175,6 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     {
         int can = 0;
         if (hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, c->device) != hipSuccess) (void)hipGetLastError();
-#ifdef AGG_EXP_NO_WAITVALUE
-        can = 0;
-#endif
         c->can_wait_value = can;
     }
     if ((rc = hip_fail(hipMalloc((void**)&c->staging, (size_t)world_size * shard_bytes))) != AGG_OK) goto fail;
@@ -413,7 +410,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
         loc.rank_of[0] = a.rank_of[local_job];
         return hip_fail(launch_producer(loc, nwg, st));
     }
-    // copy engine: one transfer per chunk, then "another data transfer solely for signals" (Section 3.6)
+    // copy engine: one transfer per chunk, then a second, tiny transfer that carries only the signal (Section 3.6)
     if (!c->device_epoch) HIP_TRY(launch_signal_set(c->epoch_word, c->epoch, nullptr, st));   // else the word is the epoch already
     for (int j = 0; j < a.n_jobs; ++j) {
         const int r = a.rank_of[j];

@@ -66,11 +66,7 @@ __device__ __forceinline__ void static_for(F&& f)
 template <int BLK>
 __device__ __forceinline__ void mfma_acc(const bf16x8& a, const bf16x8& b)
 {
-#ifdef AGG_EXP_NO_MFMA
-    asm volatile("; no mfma %2 %3" ::"v"(a), "v"(b), "n"(BLK * 16), "n"(BLK * 16 + 15));
-#else
     asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3]" ::"v"(a), "v"(b), "n"(BLK * 16), "n"(BLK * 16 + 15));
-#endif
 }
 template <int R>
 __device__ __forceinline__ void acc_zero()
@@ -85,9 +81,6 @@ __device__ __forceinline__ float acc_read()
     return x;
 }
 
-#ifndef AGG_LOAD_AUX
-#define AGG_LOAD_AUX 0                 // cache policy bits of the global->LDS loads
-#endif
 constexpr int BK = 64;                 // bf16 per stage
 constexpr int ROW_BYTES = BK * 2;      // 128-byte rows in LDS: one cache line per row and stage
 constexpr int UNIT_ROWS = 8;           // one wave-wide 16-byte-per-lane load covers 8 rows
@@ -107,10 +100,7 @@ struct Cfg {
     // The LDS ring holds RW loads per wave (4 KiB each: the same load of all four waves), a stage is L of them.
     // RW >= 2 L; RW need not be a multiple of L: the stream of loads simply wraps around the ring, so that the
     // whole LDS is used as look-ahead even when only 2 1/3 stages fit.
-#ifndef AGG_RING_BIG
-#define AGG_RING_BIG 35
-#endif
-    static constexpr int RW = (BN == 256) ? 36 : (BM == 256) ? AGG_RING_BIG : 32;
+    static constexpr int RW = (BN == 256) ? 36 : (BM == 256) ? 35 : 32;
     static constexpr int RING_BYTES = RW * 4096;
     static constexpr int PERIOD = std::lcm(L, RW) / L;     // stages after which ring positions repeat
     // epilogue staging: each wave stages 32 rows x BN columns at a time
@@ -127,10 +117,7 @@ struct Cfg {
     // fragment reads of the next quarter-step.  They are dealt out QUOTA per MFMA slot.
     static constexpr int SLOTS = MB * NB;
     static constexpr int F = MB + NB;
-#ifndef AGG_LOAD_QUARTERS
-#define AGG_LOAD_QUARTERS 3
-#endif
-    static constexpr int LQ = (L + AGG_LOAD_QUARTERS - 1) / AGG_LOAD_QUARTERS;   // loads per quarter-step while a batch is issued
+    static constexpr int LQ = (L + 2) / 3;   // loads per quarter-step while a batch is issued
     static constexpr int QUOTA = (LQ + F + SLOTS - 1) / SLOTS;
 };
 
@@ -256,18 +243,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
 
         // ---- per-tile buffer descriptors and per-lane load offsets (bytes from the tile's A / B origin);
         // rows past the edge of the matrix fall outside the descriptor and load as zero
-#ifdef AGG_EXP_SAMETILE      // experiment: every workgroup loads the operands of tile (0, 0): all L2 hits, no HBM traffic
-        const int m0l = 0, n0l = 0;
-#else
-        const int m0l = m0, n0l = n0;
-#endif
         const __amdgpu_buffer_rsrc_t a_rsrc =
             GROUPED ? make_rsrc(p.A, p.a_bytes)
-                    : make_rsrc((from_local ? p.A_local + (long long)(m0l - p.local_lo) * p.lda : p.A + (long long)m0l * p.lda),
-                                (unsigned)(min(BM, p.M - m0l) * (int)p.lda * 2));
+                    : make_rsrc((from_local ? p.A_local + (long long)(m0 - p.local_lo) * p.lda : p.A + (long long)m0 * p.lda),
+                                (unsigned)(min(BM, p.M - m0) * (int)p.lda * 2));
         const __amdgpu_buffer_rsrc_t b_rsrc =
-            make_rsrc(p.B + (GROUPED ? (long long)expert * p.b_group_stride : 0ll) + (long long)n0l * p.ldb,
-                      (unsigned)(min(BN, p.N - n0l) * (int)p.ldb * 2));
+            make_rsrc(p.B + (GROUPED ? (long long)expert * p.b_group_stride : 0ll) + (long long)n0 * p.ldb,
+                      (unsigned)(min(BN, p.N - n0) * (int)p.ldb * 2));
         // unit i of this wave is unit u = wave + 4i of the stage: A units first, then B units
         unsigned ld_off[L];
 #pragma unroll
@@ -294,7 +276,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
             constexpr bool is_a = 4 * i < C_::A_UNITS;      // the same for all four waves
             unsigned char* dst = lds + pos * 4096 + wave * 1024;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
-                                                     ks * ROW_BYTES, 0, AGG_LOAD_AUX);
+                                                     ks * ROW_BYTES, 0, 0);
         };
 
         // two fragment sets, one per parity of the quarter-step.  Fragment f < MB is the A fragment of row
@@ -313,9 +295,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
             fr[set][f] = *(const bf16x8*)(lds + pos * 4096 + fr_off[h]);
         };
 
-#ifdef AGG_EXP_TIMING
-        const long long tt0 = __builtin_readcyclecounter();
-#endif
         static_for<C_::ACC>([&](auto r) { acc_zero<decltype(r)::value>(); });
 
         // ---- prologue: the first RW - L + LQ loads of the stream (stage 0, stage 1, the head of stage 2 ...);
@@ -330,20 +309,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
         __builtin_amdgcn_s_barrier();
         static_for<MB + NB>([&](auto f_c) { read_frag(f_c, std::integral_constant<int, 0>{}, 0, 0); });
 
-        // experiment switches (never defined in the product build): drop work from the main loop to see what it costs
-#ifdef AGG_EXP_NO_LDSREAD
-#define LOOP_READ_FRAG(...) ((void)0)
-#else
-#define LOOP_READ_FRAG(...) read_frag(__VA_ARGS__)
-#endif
-#ifdef AGG_EXP_NO_GLOAD
-#define LOOP_LOAD_UNIT(...) ((void)0)
-#else
-#define LOOP_LOAD_UNIT(...) load_unit(__VA_ARGS__)
-#endif
-#ifdef AGG_EXP_TIMING
-        const long long tt1 = __builtin_readcyclecounter();
-#endif
         // ---- main loop, PERIOD stages per pass so that ring positions are constants.  The MFMAs are volatile
         // asm, so memory operations keep their place between them: the order below is the schedule.  Slot q of
         // a quarter-step works on column block q / MB, row block q % MB; the B fragment is the first MFMA
@@ -377,7 +342,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                                 // the quarter before the barrier issues no loads: its fragment reads go first, so
                                 // that they are back when the wave reaches the barrier
                                 if constexpr (o < C_::F)
-                                    LOOP_READ_FRAG(std::integral_constant<int, o>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
+                                    read_frag(std::integral_constant<int, o>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
                             } else if constexpr (o < LQ) {
                                 // quarter 3 starts the batch released by this stage's barrier (j-th load of the
                                 // batch: stream index ks*L + RW + j); quarters 0 and 1 finish the batch released by
@@ -385,41 +350,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                                 if constexpr (h == QS - 1) {
                                     constexpr int j = o;
                                     if constexpr (j < L)
-                                        LOOP_LOAD_UNIT(std::integral_constant<int, (RW + j) % L>{},
+                                        load_unit(std::integral_constant<int, (RW + j) % L>{},
                                                        std::integral_constant<int, (base_cur + j) % RW>{},
                                                        min(ks + (RW + j) / L, KS - 1));
                                 } else {
                                     constexpr int j = (h + 1) * LQ + o;
                                     if constexpr (j < L)
-                                        LOOP_LOAD_UNIT(std::integral_constant<int, (RW + j) % L>{},
+                                        load_unit(std::integral_constant<int, (RW + j) % L>{},
                                                        std::integral_constant<int, (base_prev + j) % RW>{},
                                                        min(ks - 1 + (RW + j) / L, KS - 1));
                                 }
                             } else if constexpr (o - LQ < C_::F) {
                                 constexpr int f = o - LQ;
                                 if constexpr (h < QS - 1)
-                                    LOOP_READ_FRAG(std::integral_constant<int, f>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
+                                    read_frag(std::integral_constant<int, f>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
                                 else
-                                    LOOP_READ_FRAG(std::integral_constant<int, f>{}, std::integral_constant<int, base_next>{}, 0, 1 - set);
+                                    read_frag(std::integral_constant<int, f>{}, std::integral_constant<int, base_next>{}, 0, 1 - set);
                             }
                         });
                     });
                     if constexpr (h == QS - 2) {
-#ifndef AGG_EXP_NO_BARRIER
                         // stage ks+1 has landed for this wave (all but the RW - 2L youngest loads are back), its own
                         // fragment reads of this stage are back; after the barrier that holds for all waves
                         __builtin_amdgcn_s_waitcnt(vmcnt_imm(RW - 2 * L) & ~(0xF << 8));     // and lgkmcnt(0)
                         __builtin_amdgcn_s_barrier();
-#endif
                     }
                 });
                 if (ks + 1 >= KS) done = true;
             });
             if (done) break;
         }
-#ifdef AGG_EXP_TIMING
-        const long long tt2 = __builtin_readcyclecounter();
-#endif
 
         // ---- epilogue.  Accumulator block (i, j) is the transposed block: lane l holds output row
         // i*32 + l%32 and, in register v, column j*32 + 8*(v/4) + 4*(l/32) + v%4 -- four consecutive columns per
@@ -427,9 +387,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
         asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7");     // the last MFMAs retire before the read-out
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));              // the last (redundant) loads have landed in LDS
         __syncthreads();                                       // and every wave is done with the ring
-#ifdef AGG_EXP_TIMING
-        const long long tta = __builtin_readcyclecounter();
-#endif
         {
             int lane_e = lane;
             asm volatile("" : "+v"(lane_e));     // keeps the address arithmetic below inside the tile loop
@@ -567,9 +524,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
             if (p.c_is_f32) epilogue(float{}); else epilogue(__bf16{});
         }
 
-#ifdef AGG_EXP_TIMING
-        const long long ttb = __builtin_readcyclecounter();
-#endif
         // GEMM-RS: count this tile for every chunk of every slice it touches; the last tile of a chunk raises the
         // chunk's signal (the notify of Algorithm 3: those rows are complete where their reducer will read them)
         if (!GROUPED && p.n_slices && p.slice_ctr) {
@@ -610,14 +564,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
         // those waits stricter.
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only (vmcnt and expcnt fields at their no-wait maximum)
         __builtin_amdgcn_s_barrier();
-#ifdef AGG_EXP_TIMING
-        if (tid == 0 && (g == 0 || g == 100)) {
-            const long long tt3 = __builtin_readcyclecounter();
-            long long* dbg = (long long*)(p.err + 8) + (g ? 4 : 0);
-            dbg[0] = tt1 - tt0; dbg[1] = tt2 - tt1; dbg[2] = tt3 - tt2; dbg[3] = KS;
-            if (g == 0) { dbg[8] = tta - tt2; dbg[9] = ttb - tta; dbg[10] = tt3 - ttb; }
-        }
-#endif
     }
 #else
     (void)p;

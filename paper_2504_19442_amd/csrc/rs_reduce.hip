@@ -149,12 +149,6 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs a)
 // a GEMM workgroup has finished).  All variants but <8, 2> are that small.
 hipError_t launch_reduce(const ReduceArgs& a, int n_workgroups, hipStream_t stream, bool beside_gemm)
 {
-#ifdef AGG_EXP_REDUCE_BIG
-    beside_gemm = false;
-#endif
-#ifdef AGG_EXP_REDUCE_SMALL
-    beside_gemm = true;
-#endif
     if (a.W == 8 && beside_gemm) {
         hipLaunchKernelGGL((reduce_kernel<8, 1>), dim3(n_workgroups), dim3(256), 0, stream, a);
         return hipGetLastError();

@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2504_19442_amd as agg
 import workloads as wl
-from gpu_util import AgGemmRun
+from harness import AgGemmRun
 
 pytestmark = pytest.mark.gpu
 
@@ -69,7 +69,7 @@ def test_run_recorded_in_a_graph_replays_with_a_fresh_epoch_each_time():
 
 def test_gemm_rs_recorded_in_a_graph():
     """GEMM + ReduceScatter for one rank: reset, the peers' signals, the GEMM and the reducer in one graph."""
-    from gpu_util import dev_bf16
+    from harness import dev_bf16
     sh = wl.RS_TINY
     rank = 2
     inp = wl.make_gemm_rs(sh, rank=rank)

@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2504_19442_amd as agg
 import workloads as wl
-from gpu_util import dev_bf16, host_bits, _tensor_from_ptr
+from harness import dev_bf16, host_bits, _tensor_from_ptr
 
 pytestmark = pytest.mark.gpu
 
@@ -62,11 +62,11 @@ class MoeRun:
         self.ctx.free()
 
 
-def _check_y(Y, want, K, scale=1.0):
+def _check_y(Y, want, K):
     got = Y.astype(np.float64)
     rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
     assert rel <= 1e-4, rel
-    assert np.abs(got - want).max() <= 1e-3 * np.sqrt(K) * max(1.0, scale)
+    assert np.abs(got - want).max() <= 1e-3 * np.sqrt(K)
 
 
 @pytest.mark.parametrize("rank", [0, 2])
@@ -199,7 +199,7 @@ def test_moe_argument_errors():
         run.close()
 
 
-def test_moe_full_size_sampled_rows():
+def test_moe_full_size_whole_output():
     sh = wl.MOE_FULL
     inp = wl.make_moe(sh)
     rank = 3
@@ -209,16 +209,11 @@ def test_moe_full_size_sampled_rows():
         Y, tok, seg = run.run(out_dtype=agg.F32)
         assert np.array_equal(tok, tok_ref)
         assert np.array_equal(seg.astype(np.int64), seg_ref)
-        rng = np.random.default_rng(8)
-        P = sh.T * sh.topk
-        # rows at segment starts and ends (tile edges) plus random ones
-        rows = np.unique(np.concatenate([seg_ref[:-1][:8], seg_ref[1:][:8] - 1, rng.choice(P, size=16, replace=False)]))
-        want = oracle.moe_gemm(inp.shards, inp.W_ekn, inp.topk_ids, rank, rows=rows)
-        y = Y[torch.from_numpy(rows).cuda()].cpu().numpy()
-        _check_y(y, want, sh.K)
+        # every row of Y (all experts, all tiles) against the oracle
+        want = oracle.moe_gemm(inp.shards, inp.W_ekn, inp.topk_ids, rank)
+        _check_y(Y.cpu().numpy(), want, sh.K)
         Y2, _, _ = run.run(out_dtype=agg.F32, order=list(wl.arrival_orders(sh.W, rank, limit=2, seed=4)[-1]),
                            consumer_first=False)
         assert torch.equal(Y, Y2)
-        assert not torch.isnan(Y).any()
     finally:
         run.close()

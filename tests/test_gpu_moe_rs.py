@@ -6,7 +6,7 @@ import torch
 import oracle
 import paper_2504_19442_amd as agg
 import workloads as wl
-from gpu_util import dev_bf16
+from harness import dev_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -71,7 +71,7 @@ class MoeRsRun:
 def _close(got, want, K):
     rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
     assert rel <= 1e-4, rel
-    assert np.abs(got - want).max() <= 1e-3 * np.sqrt(K) * max(1.0, float(np.abs(want).max()))
+    assert np.abs(got - want).max() <= 1e-3 * np.sqrt(K)
 
 
 @pytest.mark.parametrize("rank", [0, 2])
@@ -114,7 +114,7 @@ def test_moe_rs_tiny(rank, tile):
             _close(z[other * Tr:(other + 1) * Tr].astype(np.float64), ref, sh.Kl)
         # bf16 result = RNE of the fp32 result; Z_other may be left out
         Rb, _ = run.run(True, with_other=False, r_dtype=agg.BF16, tile=tile)
-        from gpu_util import host_bits
+        from harness import host_bits
         assert np.array_equal(host_bits(Rb), wl.f32_to_bf16_bits(base))
     finally:
         run.close()
@@ -158,11 +158,11 @@ def test_moe_rs_argument_errors():
         run.close()
 
 
-def test_moe_rs_full_size_sampled_tokens():
+def test_moe_rs_full_size_all_tokens_of_the_rank():
     sh = wl.MOE_RS_FULL
     rank = 6
     inp = wl.make_moe_rs(sh, rank=rank)
-    rows = np.sort(np.random.default_rng(9).choice(sh.tokens_per_rank, size=48, replace=False))
+    rows = np.arange(sh.tokens_per_rank)          # the whole of R
     want = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, inp.peer_slots, sh.W, rank, rows=rows)
     run = MoeRsRun(inp, rank)
     try:

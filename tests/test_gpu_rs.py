@@ -1,7 +1,7 @@
 """GPU parity of the ReduceScatter reducer and of GEMM-ReduceScatter against the CPU oracle, through the C ABI.
 
 Bars: the reducer is bit-exact against the oracle's ordered fp32 sum (Algorithm 3, stream 2) whatever the order
-in which the slots' signals are raised; GEMM-RS is within rel. Frobenius 1e-4 and max abs 1e-3*sqrt(K)*scale of
+in which the slots' signals are raised; GEMM-RS is within rel. Frobenius 1e-4 and max abs 1e-3*sqrt(K) of
 the fp64 oracle, and bit-identical across signal orders.
 """
 import itertools
@@ -14,7 +14,7 @@ import torch
 import oracle
 import paper_2504_19442_amd as agg
 import workloads as wl
-from gpu_util import dev_bf16, host_bits
+from harness import dev_bf16, host_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -213,10 +213,9 @@ def _gemm_rs_case(shape, rank, rows_own, rows_other, tile=None, with_other=True,
         # own slice + peers against the fp64 oracle
         want = oracle.gemm_rs(inp.A_loc, inp.B_kn, inp.peer_slots, W, rank, rows=rows_own)
         got = R0[rows_own].astype(np.float64)
-        scale = max(1.0, float(np.abs(want).max()))
         rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
         assert rel <= 1e-4, rel
-        assert np.abs(got - want).max() <= 1e-3 * np.sqrt(Kl) * scale
+        assert np.abs(got - want).max() <= 1e-3 * np.sqrt(Kl)
         # the slot the GEMM wrote is exactly what the reducer added: R - peers (in order) is reproducible on the host
         own = run.slots[rank].cpu().numpy()
         ordered = [inp.peer_slots[w] if w != rank else own for w in range(W)]
@@ -228,6 +227,7 @@ def _gemm_rs_case(shape, rank, rows_own, rows_other, tile=None, with_other=True,
             gotP = P[torch.from_numpy(rows_other).cuda()].cpu().numpy().astype(np.float64)
             relP = np.linalg.norm(gotP - wantP) / max(np.linalg.norm(wantP), 1e-30)
             assert relP <= 1e-4, relP
+            assert np.abs(gotP - wantP).max() <= 1e-3 * np.sqrt(Kl)
             # rows of the own slice are never written to P_other
             assert torch.isnan(P[rank * Ms:(rank + 1) * Ms]).all()
     finally:
@@ -256,13 +256,15 @@ def test_gemm_rs_tiny_with_chunk_signals(chunks, with_other, own_last):
 
 
 @pytest.mark.parametrize("chunks,own_last", [(1, False), (4, False), (4, True), (1, True)])
-def test_gemm_rs_full_size_sampled_rows(chunks, own_last):
+def test_gemm_rs_full_size(chunks, own_last):
+    # every row of the own slice (all of R), and of the other slices one row out of every 128-row block (the smallest
+    # tile height), so that every m-tile of the launch is compared with the oracle
     sh = wl.RS_FULL
     rank = 5
     rng = np.random.default_rng(5)
-    rows_own = np.sort(rng.choice(sh.Ms, size=12, replace=False))
-    rows_other = np.sort(rng.choice(np.setdiff1d(np.arange(sh.M), np.arange(rank * sh.Ms, (rank + 1) * sh.Ms)),
-                                    size=12, replace=False))
+    rows_own = np.arange(sh.Ms)
+    own = set(range(rank * sh.Ms, (rank + 1) * sh.Ms))
+    rows_other = np.array([b + int(rng.integers(0, 128)) for b in range(0, sh.M, 128) if b not in own], dtype=np.int64)
     _gemm_rs_case(sh, rank, rows_own, rows_other, orders=2, chunks=chunks, own_last=own_last)
 
 
@@ -317,7 +319,7 @@ def _all_ranks_gemm_rs(shape, reducers_first, tile=None, rows=None, chunks=1):
         g = got[rows]
         rel = np.linalg.norm(g - want) / np.linalg.norm(want)
         assert rel <= 1e-4, rel
-        assert np.abs(g - want).max() <= 1e-3 * np.sqrt(W * Kl) * max(1.0, float(np.abs(want).max()))
+        assert np.abs(g - want).max() <= 1e-3 * np.sqrt(W * Kl)
     finally:
         for rr in ranks:
             rr.close()
@@ -467,7 +469,7 @@ def test_all_ranks_pull_mode(chunks):
         got = torch.cat(R).cpu().numpy().astype(np.float64)
         want = oracle.gemm(A_cat, B_cat)
         assert np.linalg.norm(got - want) / np.linalg.norm(want) <= 1e-4
-        assert np.abs(got - want).max() <= 1e-3 * np.sqrt(W * Kl) * max(1.0, float(np.abs(want).max()))
+        assert np.abs(got - want).max() <= 1e-3 * np.sqrt(W * Kl)
     finally:
         for rr in ranks:
             rr.close()
