@@ -21,43 +21,49 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-i
          "-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"]
 
 
-def check_agprs() -> None:
-    """Compile the GEMM kernel to assembly and fail if the compiler itself touches an accumulator register
+def check_agprs(asm_path: str) -> None:
+    """Fail if, in the device assembly of a GEMM translation unit, the compiler itself touches an accumulator register
     (any a<N> outside the inline-asm blocks), or if a kernel spills to scratch."""
     import re
-    src = os.path.join(CSRC, "gemm_kernel.hip")
-    r = subprocess.run([HIPCC, *FLAGS, "--cuda-device-only", "-S", src, "-o", "-"],
-                       capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(r.stderr)
     in_asm = False
     pat = re.compile(r"(?<![A-Za-z0-9_.])a(\[\d+(:\d+)?\]|\d+\b)")
-    for n, line in enumerate(r.stdout.splitlines(), 1):
-        t = line.strip()
-        if t.startswith(";;#ASMSTART"):
-            in_asm = True
-        elif t.startswith(";;#ASMEND"):
-            in_asm = False
-        elif not in_asm and not t.startswith(";") and not t.startswith("."):
-            code = t.split(";")[0]
-            if pat.search(code):
-                raise RuntimeError(f"compiler-allocated accumulator register in gemm_kernel (asm line {n}): {t}")
-        if t.startswith("; ScratchSize:") and t.split(":")[1].strip() != "0":
-            raise RuntimeError(f"gemm_kernel spills to scratch: {t}")
+    with open(asm_path) as f:
+        for n, line in enumerate(f, 1):
+            t = line.strip()
+            if t.startswith(";;#ASMSTART"):
+                in_asm = True
+            elif t.startswith(";;#ASMEND"):
+                in_asm = False
+            elif not in_asm and not t.startswith(";") and not t.startswith("."):
+                code = t.split(";")[0]
+                if pat.search(code):
+                    raise RuntimeError(f"compiler-allocated accumulator register in {asm_path} (line {n}): {t}")
+            if t.startswith("; ScratchSize:") and t.split(":")[1].strip() != "0":
+                raise RuntimeError(f"a GEMM kernel spills to scratch ({asm_path}): {t}")
+
+
+def _is_gemm_unit(src: str) -> bool:
+    return os.path.basename(src).startswith("gemm_inst_")
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.basename(src) + ".o")
+    base = os.path.basename(src)
+    obj = os.path.join(OBJ, base + ".o")
+    asm = os.path.join(OBJ, base[:-4] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
     deps = [src] + glob.glob(os.path.join(CSRC, "*.h")) + [os.path.join(HERE, "..", "include", "agg.h")]
-    if os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps) \
-            and os.environ.get("AGG_FORCE_BUILD") != "1":
-        return obj
-    r = subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
-    if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed on {src}:\n{err}")
-    if err.strip():
-        sys.stderr.write(err + "\n")
+    fresh = os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps) \
+        and os.environ.get("AGG_FORCE_BUILD") != "1"
+    if not fresh:
+        # the GEMM units keep their device assembly (-save-temps) for the accumulator-register check below
+        extra = ["-save-temps=obj"] if _is_gemm_unit(src) else []
+        r = subprocess.run([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj], capture_output=True, text=True, cwd=OBJ)
+        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+        if err.strip():
+            sys.stderr.write(err + "\n")
+    if _is_gemm_unit(src):
+        check_agprs(asm)
     return obj
 
 
@@ -67,11 +73,10 @@ def build(force: bool = True) -> str:
         os.environ["AGG_FORCE_BUILD"] = "1"
     try:
         srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-        with ThreadPoolExecutor(max_workers=4) as ex:
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 4)) as ex:
             objs = list(ex.map(_compile, srcs))
     finally:
         os.environ.pop("AGG_FORCE_BUILD", None)
-    check_agprs()
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB + ".tmp"], check=True)
     os.replace(LIB + ".tmp", LIB)
     return LIB

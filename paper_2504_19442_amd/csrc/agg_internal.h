@@ -89,12 +89,14 @@ struct TopkReduceArgs {
 hipError_t launch_topk_reduce(const TopkReduceArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream_t stream);
 
-enum TileConfig { TILE_256x224 = 0, TILE_128x128 = 1, TILE_256x256 = 2, TILE_128x256 = 3, TILE_CONFIGS };
+// A tile configuration = a tile shape (bits 0-1) and the MFMA form of the main loop (bit 2): v_mfma_f32_32x32x16_bf16,
+// or, with TILE_K32, v_mfma_f32_16x16x32_bf16 (half the accumulator traffic per flop: the chip holds a higher clock).
+enum TileConfig { TILE_256x224 = 0, TILE_128x128 = 1, TILE_256x256 = 2, TILE_128x256 = 3, TILE_K32 = 4, TILE_CONFIGS = 8 };
 
 struct TileShape { int bm, bn; };
 inline TileShape tile_shape(int cfg)
 {
-    switch (cfg) {
+    switch (cfg & 3) {
         case TILE_256x224: return {256, 224};
         case TILE_256x256: return {256, 256};
         case TILE_128x256: return {128, 256};

@@ -28,6 +28,7 @@
 // capped so that the kernel takes 448 of the 512 registers of a SIMD.  The 64 left over are what lets one
 // wave of a small kernel (the producer's copy waves, the reducer) run beside a consumer wave on every
 // SIMD: communication and computation share all CUs instead of splitting them (Section 3.8).
+#pragma once
 #include "agg_internal.h"
 
 #include <numeric>
@@ -67,6 +68,12 @@ template <int BLK>
 __device__ __forceinline__ void mfma_acc(const bf16x8& a, const bf16x8& b)
 {
     asm volatile("v_mfma_f32_32x32x16_bf16 a[%2:%3], %0, %1, a[%2:%3]" ::"v"(a), "v"(b), "n"(BLK * 16), "n"(BLK * 16 + 15));
+}
+// the 16x16x32 form: block b is a[4b : 4b+3]
+template <int BLK>
+__device__ __forceinline__ void mfma_acc16(const bf16x8& a, const bf16x8& b)
+{
+    asm volatile("v_mfma_f32_16x16x32_bf16 a[%2:%3], %0, %1, a[%2:%3]" ::"v"(a), "v"(b), "n"(BLK * 4), "n"(BLK * 4 + 3));
 }
 template <int R>
 __device__ __forceinline__ void acc_zero()
@@ -119,13 +126,64 @@ struct Cfg {
     static constexpr int F = MB + NB;
     static constexpr int LQ = (L + 2) / 3;   // loads per quarter-step while a batch is issued
     static constexpr int QUOTA = (LQ + F + SLOTS - 1) / SLOTS;
+
+    // ---- the 16x16x32 form of the main loop (MF = 16).  A stage is two half-steps of K = 32; a half-step is NB16 groups
+    // of MB16 MFMAs, group j working on the B fragment of column block j and all MB16 A fragments of the wave.
+    static constexpr int MB16 = TM / 16;
+    static constexpr int NB16 = BN / 16;
+    static constexpr int DLY = 3;                // the stage's barrier sits after group DLY - 1 of the second half-step
+    static constexpr int LH1 = (NB16 - DLY < L) ? NB16 - DLY : L;   // loads issued in the rest of that half-step, one per group
+    static constexpr int LH0 = L - LH1;          // the others: in the first groups of the next stage's first half-step
+    static constexpr int P0 = RW - L + LH1;      // loads issued by the prologue
+    static_assert(LH0 <= NB16 && P0 >= L && P0 <= 63, "load schedule of the 16x16x32 loop");
+    static_assert(DLY + MB16 <= NB16, "the reads of the next A fragments fit between the barrier and the end of the half-step");
+    struct Op { int type, idx; };                // 0 none, 1 read B fragment idx, 2 read A fragment idx, 3 global->LDS load idx
+    static constexpr int NS = NB16 * MB16;       // MFMA slots per half-step: slot s = group s / MB16, row block s % MB16
+    static constexpr int SB = DLY * MB16 - 1;    // the barrier follows the MFMA of this slot (second half-step)
+    static constexpr int PER_SLOT = 3;
+    struct Slots { Op op[NS][PER_SLOT]; bool complete; };
+    // The memory operations of half-step h, placed behind the MFMA slots.  Each has an earliest slot: the refill of B
+    // register set j after the last MFMA of group j (and, in the second half-step, not before the barrier); the reads
+    // of the next A fragments one per group from group DLY on; the global->LDS loads one per group, from the barrier on.  They are
+    // taken in that order, one per slot, two when three or more are ready; the last slot takes whatever is left.
+    static constexpr Slots make_slots(int h)
+    {
+        Op ops[64] = {};
+        int early[64] = {};
+        int n = 0;
+        for (int j = 0; j < NB16; ++j) {
+            int e = j * MB16 + MB16 - 1;
+            if (h == 1 && e < SB) e = SB;
+            ops[n] = Op{1, j}; early[n++] = e;
+        }
+        for (int ia = 0; ia < MB16; ++ia) { ops[n] = Op{2, ia}; early[n++] = (DLY + ia) * MB16; }
+        if (h == 1) for (int jj = 0; jj < LH1; ++jj) { ops[n] = Op{3, jj}; early[n++] = SB + jj * MB16; }
+        else for (int j = 0; j < LH0; ++j) { ops[n] = Op{3, LH1 + j}; early[n++] = j * MB16; }
+        for (int a = 1; a < n; ++a)                      // stable insertion sort by earliest slot
+            for (int b = a; b > 0 && early[b - 1] > early[b]; --b) {
+                const Op to = ops[b]; ops[b] = ops[b - 1]; ops[b - 1] = to;
+                const int te = early[b]; early[b] = early[b - 1]; early[b - 1] = te;
+            }
+        Slots S{};
+        int next = 0;
+        for (int s = 0; s < NS; ++s) {
+            int ready = 0;
+            for (int k = next; k < n && early[k] <= s; ++k) ++ready;
+            int take = ready >= 3 ? 2 : (ready >= 1 ? 1 : 0);
+            if (s == NS - 1) take = ready < PER_SLOT ? ready : PER_SLOT;
+            for (int k = 0; k < take; ++k) S.op[s][k] = ops[next++];
+        }
+        S.complete = next == n;
+        return S;
+    }
+    static_assert(make_slots(0).complete && make_slots(1).complete, "every memory operation of a half-step has a slot");
 };
 
 // Register budget: 448 of the 512 registers a SIMD has (see the file comment).
 // GROUPED = the MoE grouped GEMM (Section 4.1): tiles come from a table built on the device, rows of A are gathered
 // through row_index, B is the tile's expert's matrix, and rows at or past the tile's segment end are neither loaded
 // (they read as zero) nor stored.
-template <int BM, int BN, bool GROUPED>
+template <int BM, int BN, bool GROUPED, int MF>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gemm_kernel(const GemmParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)    // the body names gfx950 registers; the host pass only needs the launch stub
@@ -149,10 +207,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
     const int ld_chunk_even = (lane & 7) ^ ((lane >> 4) & 7);
     const int ld_chunk_odd = (lane & 7) ^ ((4 + (lane >> 4)) & 7);
     // LDS->VGPR fragments of quarter-step h: lane l reads row l%32, chunk 2h + l/32, from slot chunk ^ ((row>>1)&7)
-    int fr_off[QS];
+    // (MF = 16: fragments are 16 rows x K = 32; in half-step h lane l reads row l%16, chunk 4h + l/16)
+    int fr_off[MF == 16 ? 2 : QS];
+    if constexpr (MF == 16) {
 #pragma unroll
-    for (int h = 0; h < QS; ++h)
-        fr_off[h] = (lane & 31) * ROW_BYTES + (((2 * h + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+        for (int h = 0; h < 2; ++h)
+            fr_off[h] = (lane & 15) * ROW_BYTES + (((4 * h + (lane >> 4)) ^ ((lane >> 1) & 7)) << 4);
+    } else {
+#pragma unroll
+        for (int h = 0; h < QS; ++h)
+            fr_off[h] = (lane & 31) * ROW_BYTES + (((2 * h + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+    }
 
     const int KS = p.K / BK;             // stages
     // the epoch the signals are compared with: the host's value at launch, or (for launches recorded in a HIP graph)
@@ -218,27 +283,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
 
         // ---- wait for the signals covering rows [m0, min(m0+BM, M))  (wait + consume_token, Section 2.2)
         if (p.flags && f_hi >= f_lo) {
+            // Wave 0 polls (lane l takes signals f_lo + l, f_lo + l + 64, ...) and, once it has seen them all, executes
+            // the acquire: the wave that observed the signals is the wave that orders the loads of A after them.  The
+            // acquire invalidates this CU's L1 and this XCD's L2 lines of remotely written memory, so that no load of
+            // A below is served from a line cached before the data arrived; one wave does it for the workgroup
+            // (invalidates from all waves of all CUs queue up behind each other at the L2), and the barrier holds the
+            // other waves back until it is done.
             int gave_up = 0;
-            for (int f = f_lo + tid; f <= f_hi; f += 256) {
-                const int* fp = p.flags + (long long)f * kSignalStride;
-                const long long t0 = wall_clock64();
-                while (__hip_atomic_load(fp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
-                    if (__hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
-                        wall_clock64() - t0 > p.wait_ticks) {
-                        gave_up = 1;
-                        break;
+            if (wave == 0) {
+                for (int f = f_lo + lane; f <= f_hi; f += 64) {
+                    const int* fp = p.flags + (long long)f * kSignalStride;
+                    const long long t0 = wall_clock64();
+                    while (__hip_atomic_load(fp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
+                        if (__hip_atomic_load(p.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
+                            wall_clock64() - t0 > p.wait_ticks) {
+                            gave_up = 1;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
                     }
-                    __builtin_amdgcn_s_sleep(1);
                 }
+                if (gave_up) __hip_atomic_store(p.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             }
-            if (gave_up) __hip_atomic_store(p.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (__syncthreads_or(gave_up)) return;   // the launch drains; agg_status reports the time-out
-            // Every signal has been seen: acquire, so that no load of A below is served from a line cached
-            // before the data arrived.  The acquire invalidates this CU's L1 and this XCD's L2 lines of
-            // remotely written memory; one wave does it for the workgroup (invalidates from all waves of all
-            // CUs queue up behind each other at the L2), the barrier holds the others back until it is done.
-            if (wave == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            __syncthreads();
         }
 
         // ---- per-tile buffer descriptors and per-lane load offsets (bytes from the tile's A / B origin);
@@ -279,106 +347,210 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                                                      ks * ROW_BYTES, 0, 0);
         };
 
-        // two fragment sets, one per parity of the quarter-step.  Fragment f < MB is the A fragment of row
-        // block f, fragment MB + j the B fragment of column block j.  The 32 rows of a fragment are the k-th
-        // load of the stage (of all four waves), at ring position (base + k) mod RW, base = stage * L mod RW.
-        bf16x8 fr[2][MB + NB];
-        auto read_frag = [&](auto f_c, auto base_c, int h, int set) {
-            constexpr int f = decltype(f_c)::value, base = decltype(base_c)::value;
-            int pos;
-            if constexpr (f < MB) {
-                pos = base + wave * MB + f;                  // wave-uniform
-                if (pos >= C_::RW) pos -= C_::RW;
-            } else {
-                pos = (base + C_::A_UNITS / 4 + (f - MB)) % C_::RW;
-            }
-            fr[set][f] = *(const bf16x8*)(lds + pos * 4096 + fr_off[h]);
-        };
-
         static_for<C_::ACC>([&](auto r) { acc_zero<decltype(r)::value>(); });
 
-        // ---- prologue: the first RW - L + LQ loads of the stream (stage 0, stage 1, the head of stage 2 ...);
-        // the main loop's first quarter-steps continue the stream from there.  A stage past the end re-loads
-        // the last one: harmless, and it keeps the count of outstanding loads the same on every path.
-        constexpr int RW = C_::RW, PERIOD = C_::PERIOD, LQ = C_::LQ;
-        static_for<RW - L + LQ>([&](auto n_c) {
-            constexpr int n = decltype(n_c)::value;
-            load_unit(std::integral_constant<int, n % L>{}, std::integral_constant<int, n % RW>{}, min(n / L, KS - 1));
-        });
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(RW - 2 * L + LQ));     // stage 0 has landed
-        __builtin_amdgcn_s_barrier();
-        static_for<MB + NB>([&](auto f_c) { read_frag(f_c, std::integral_constant<int, 0>{}, 0, 0); });
+        if constexpr (MF == 16) {
+            // ---- the 16x16x32 form.  Half-step h of a stage covers chunks 4h .. 4h+3 of the stage's rows (K = 32).  The A
+            // fragments of the running half-step are fa[h], the next half-step's go into fa[1 - h] while it runs; the B
+            // fragment of column block j lives in fb[j], which is free again after the MB16 MFMAs of group j and is
+            // refilled at once with the next half-step's fragment j -- one set of B registers, not two.
+            constexpr int MB16 = C_::MB16, NB16 = C_::NB16;
+            constexpr int RW = C_::RW, PERIOD = C_::PERIOD;
+            bf16x8 fa[2][MB16], fb[NB16];
+            // A fragment i of this wave is 16-row block wave * MB16 + i of the tile's A rows; B fragment j is 16-row block
+            // j of its B rows.  Two 16-row blocks share a ring position (the same load of all four waves = 32 rows).
+            auto read_a = [&](auto i_c, auto base_c, auto h_c, int set) {
+                constexpr int i = decltype(i_c)::value, base = decltype(base_c)::value, h = decltype(h_c)::value;
+                const int rb = wave * MB16 + i;                  // wave-uniform
+                int pos = base + (rb >> 1);
+                if (pos >= RW) pos -= RW;
+                fa[set][i] = *(const bf16x8*)(lds + pos * 4096 + (rb & 1) * 2048 + fr_off[h]);
+            };
+            auto read_b = [&](auto j_c, auto base_c, auto h_c) {
+                constexpr int j = decltype(j_c)::value, base = decltype(base_c)::value, h = decltype(h_c)::value;
+                constexpr int pos = (base + C_::A_UNITS / 4 + j / 2) % RW;
+                fb[j] = *(const bf16x8*)(lds + pos * 4096 + (j & 1) * 2048 + fr_off[h]);
+            };
 
-        // ---- main loop, PERIOD stages per pass so that ring positions are constants.  The MFMAs are volatile
-        // asm, so memory operations keep their place between them: the order below is the schedule.  Slot q of
-        // a quarter-step works on column block q / MB, row block q % MB; the B fragment is the first MFMA
-        // operand, so accumulator block (i, j) holds the transposed 32x32 block.
-        //
-        // Stage ks: quarter-steps 0..2 read ahead inside the stage; then every wave waits until its loads of
-        // stage ks+1 have landed (RW - 2L younger ones may still be in flight) and meets the others at the
-        // barrier -- all of stage ks+1 is in LDS and nobody needs stage ks any more; quarter-step 3 reads the
-        // first fragments of stage ks+1.  Each barrier releases the L ring positions of stage ks: the next L
-        // loads of the stream (load n goes where load n - RW was, and n - RW is a load of stage ks) are issued
-        // LQ per quarter-step over the next three quarter-steps.  They belong to stages ks+2 and later, so each
-        // has at least a whole stage of MFMA work to land.
-        for (int ks0 = 0;; ks0 += PERIOD) {
-            bool done = false;
-            static_for<PERIOD>([&](auto ph_c) {
-                constexpr int ph = decltype(ph_c)::value;
-                if (done) return;
-                const int ks = ks0 + ph;
-                constexpr int base_cur = (ph * L) % RW;                          // ring base of stage ks
-                constexpr int base_next = ((ph + 1) * L) % RW;                   // of stage ks+1
-                constexpr int base_prev = (((ph + PERIOD - 1) % PERIOD) * L) % RW;   // of stage ks-1
-                static_for<QS>([&](auto h_c) {
-                    constexpr int h = decltype(h_c)::value;
-                    constexpr int set = h & 1;
-                    static_for<C_::SLOTS>([&](auto q_c) {
-                        constexpr int q = decltype(q_c)::value;
-                        mfma_acc<(q % MB) * NB + q / MB>(fr[set][MB + q / MB], fr[set][q % MB]);
-                        static_for<C_::QUOTA>([&](auto k_c) {
-                            constexpr int o = q * C_::QUOTA + decltype(k_c)::value;
-                            if constexpr (h == QS - 2) {
-                                // the quarter before the barrier issues no loads: its fragment reads go first, so
-                                // that they are back when the wave reaches the barrier
-                                if constexpr (o < C_::F)
-                                    read_frag(std::integral_constant<int, o>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
-                            } else if constexpr (o < LQ) {
-                                // quarter 3 starts the batch released by this stage's barrier (j-th load of the
-                                // batch: stream index ks*L + RW + j); quarters 0 and 1 finish the batch released by
-                                // the previous stage's barrier
-                                if constexpr (h == QS - 1) {
-                                    constexpr int j = o;
-                                    if constexpr (j < L)
-                                        load_unit(std::integral_constant<int, (RW + j) % L>{},
-                                                       std::integral_constant<int, (base_cur + j) % RW>{},
-                                                       min(ks + (RW + j) / L, KS - 1));
-                                } else {
-                                    constexpr int j = (h + 1) * LQ + o;
-                                    if constexpr (j < L)
-                                        load_unit(std::integral_constant<int, (RW + j) % L>{},
-                                                       std::integral_constant<int, (base_prev + j) % RW>{},
-                                                       min(ks - 1 + (RW + j) / L, KS - 1));
-                                }
-                            } else if constexpr (o - LQ < C_::F) {
-                                constexpr int f = o - LQ;
-                                if constexpr (h < QS - 1)
-                                    read_frag(std::integral_constant<int, f>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
-                                else
-                                    read_frag(std::integral_constant<int, f>{}, std::integral_constant<int, base_next>{}, 0, 1 - set);
+            // ---- prologue: the first P0 loads of the stream (stage 0, stage 1, the head of stage 2 ...); the main loop's
+            // first groups continue the stream from there.  A stage past the end re-loads the last one: harmless, and
+            // it keeps the count of outstanding loads the same on every path.
+            static_for<C_::P0>([&](auto n_c) {
+                constexpr int n = decltype(n_c)::value;
+                load_unit(std::integral_constant<int, n % L>{}, std::integral_constant<int, n % RW>{}, min(n / L, KS - 1));
+            });
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(C_::P0 - L));     // stage 0 has landed
+            __builtin_amdgcn_s_barrier();
+            static_for<MB16>([&](auto i_c) {
+                read_a(i_c, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, 0);
+            });
+            static_for<NB16>([&](auto j_c) {
+                read_b(j_c, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+            });
+
+            // ---- main loop, PERIOD stages per pass so that ring positions are constants.  The MFMAs are volatile asm,
+            // so memory operations keep their place between them: the order below is the schedule.  The B fragment
+            // is the first MFMA operand, so accumulator block (i, j) holds the transposed 16x16 block.
+            //
+            // Stage ks: during half-step 0 every fragment of half-step 1 is read.  In half-step 1, after DLY groups (by
+            // then the wave's last reads of stage ks are long back), the wave waits until its own loads of stage ks+1
+            // have landed (RW - 2L younger ones may still be in flight) and meets the others at the barrier: all of
+            // stage ks+1 is in LDS and nobody needs stage ks any more.  From there on the fragments of stage ks+1 are
+            // read (those of the first DLY groups, held back until now, first), and the L ring positions of stage ks
+            // are refilled: load n goes where load n - RW was; LH1 of them in the rest of this half-step, one per
+            // group, the others in the first groups of the next stage.  They belong to stages ks+2 and later, so each
+            // has about a stage of MFMA work to land.
+            for (int ks0 = 0;; ks0 += PERIOD) {
+                bool done = false;
+                static_for<PERIOD>([&](auto ph_c) {
+                    constexpr int ph = decltype(ph_c)::value;
+                    if (done) return;
+                    const int ks = ks0 + ph;
+                    constexpr int base_cur = (ph * L) % RW;                              // ring base of stage ks
+                    constexpr int base_next = ((ph + 1) * L) % RW;                       // of stage ks+1
+                    constexpr int base_prev = (((ph + PERIOD - 1) % PERIOD) * L) % RW;   // of stage ks-1
+                    static_for<2>([&](auto h_c) {
+                        constexpr int h = decltype(h_c)::value;
+                        // where the next half-step's fragments are
+                        using next_base = std::integral_constant<int, h == 0 ? base_cur : base_next>;
+                        using next_h = std::integral_constant<int, 1 - h>;
+                        constexpr auto slots = C_::make_slots(h);
+                        static_for<C_::NS>([&](auto s_c) {
+                            constexpr int sl = decltype(s_c)::value;
+                            constexpr int j = sl / MB16, i = sl % MB16;
+                            mfma_acc16<i * NB16 + j>(fb[j], fa[h][i]);
+                            if constexpr (h == 1 && sl == C_::SB) {
+                                // stage ks+1 has landed for this wave (all but the RW - 2L youngest loads are back) and
+                                // its own fragment reads of stage ks are back; after the barrier that holds for all waves
+                                __builtin_amdgcn_s_waitcnt(vmcnt_imm(RW - 2 * L) & ~(0xF << 8));     // and lgkmcnt(0)
+                                __builtin_amdgcn_s_barrier();
                             }
+                            static_for<C_::PER_SLOT>([&](auto k_c) {
+                                constexpr auto op = slots.op[sl][decltype(k_c)::value];
+                                if constexpr (op.type == 1) {
+                                    read_b(std::integral_constant<int, op.idx>{}, next_base{}, next_h{});
+                                } else if constexpr (op.type == 2) {
+                                    read_a(std::integral_constant<int, op.idx>{}, next_base{}, next_h{}, 1 - h);
+                                } else if constexpr (op.type == 3) {
+                                    // load op.idx of the batch released by this stage's barrier (h = 1) or by the
+                                    // previous stage's (h = 0): stream index (stage * L) + RW + idx
+                                    constexpr int jj = op.idx;
+                                    if constexpr (h == 1)
+                                        load_unit(std::integral_constant<int, (RW + jj) % L>{},
+                                                  std::integral_constant<int, (base_cur + jj) % RW>{},
+                                                  min(ks + (RW + jj) / L, KS - 1));
+                                    else
+                                        load_unit(std::integral_constant<int, (RW + jj) % L>{},
+                                                  std::integral_constant<int, (base_prev + jj) % RW>{},
+                                                  min(ks - 1 + (RW + jj) / L, KS - 1));
+                                }
+                            });
                         });
                     });
-                    if constexpr (h == QS - 2) {
-                        // stage ks+1 has landed for this wave (all but the RW - 2L youngest loads are back), its own
-                        // fragment reads of this stage are back; after the barrier that holds for all waves
-                        __builtin_amdgcn_s_waitcnt(vmcnt_imm(RW - 2 * L) & ~(0xF << 8));     // and lgkmcnt(0)
-                        __builtin_amdgcn_s_barrier();
-                    }
+                    if (ks + 1 >= KS) done = true;
                 });
-                if (ks + 1 >= KS) done = true;
+                if (done) break;
+            }
+        } else {
+            // two fragment sets, one per parity of the quarter-step.  Fragment f < MB is the A fragment of row
+            // block f, fragment MB + j the B fragment of column block j.  The 32 rows of a fragment are the k-th
+            // load of the stage (of all four waves), at ring position (base + k) mod RW, base = stage * L mod RW.
+            bf16x8 fr[2][MB + NB];
+            auto read_frag = [&](auto f_c, auto base_c, int h, int set) {
+                constexpr int f = decltype(f_c)::value, base = decltype(base_c)::value;
+                int pos;
+                if constexpr (f < MB) {
+                    pos = base + wave * MB + f;                  // wave-uniform
+                    if (pos >= C_::RW) pos -= C_::RW;
+                } else {
+                    pos = (base + C_::A_UNITS / 4 + (f - MB)) % C_::RW;
+                }
+                fr[set][f] = *(const bf16x8*)(lds + pos * 4096 + fr_off[h]);
+            };
+
+            // ---- prologue: the first RW - L + LQ loads of the stream (stage 0, stage 1, the head of stage 2 ...);
+            // the main loop's first quarter-steps continue the stream from there.  A stage past the end re-loads
+            // the last one: harmless, and it keeps the count of outstanding loads the same on every path.
+            constexpr int RW = C_::RW, PERIOD = C_::PERIOD, LQ = C_::LQ;
+            static_for<RW - L + LQ>([&](auto n_c) {
+                constexpr int n = decltype(n_c)::value;
+                load_unit(std::integral_constant<int, n % L>{}, std::integral_constant<int, n % RW>{}, min(n / L, KS - 1));
             });
-            if (done) break;
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(RW - 2 * L + LQ));     // stage 0 has landed
+            __builtin_amdgcn_s_barrier();
+            static_for<MB + NB>([&](auto f_c) { read_frag(f_c, std::integral_constant<int, 0>{}, 0, 0); });
+
+            // ---- main loop, PERIOD stages per pass so that ring positions are constants.  The MFMAs are volatile
+            // asm, so memory operations keep their place between them: the order below is the schedule.  Slot q of
+            // a quarter-step works on column block q / MB, row block q % MB; the B fragment is the first MFMA
+            // operand, so accumulator block (i, j) holds the transposed 32x32 block.
+            //
+            // Stage ks: quarter-steps 0..2 read ahead inside the stage; then every wave waits until its loads of
+            // stage ks+1 have landed (RW - 2L younger ones may still be in flight) and meets the others at the
+            // barrier -- all of stage ks+1 is in LDS and nobody needs stage ks any more; quarter-step 3 reads the
+            // first fragments of stage ks+1.  Each barrier releases the L ring positions of stage ks: the next L
+            // loads of the stream (load n goes where load n - RW was, and n - RW is a load of stage ks) are issued
+            // LQ per quarter-step over the next three quarter-steps.  They belong to stages ks+2 and later, so each
+            // has at least a whole stage of MFMA work to land.
+            for (int ks0 = 0;; ks0 += PERIOD) {
+                bool done = false;
+                static_for<PERIOD>([&](auto ph_c) {
+                    constexpr int ph = decltype(ph_c)::value;
+                    if (done) return;
+                    const int ks = ks0 + ph;
+                    constexpr int base_cur = (ph * L) % RW;                          // ring base of stage ks
+                    constexpr int base_next = ((ph + 1) * L) % RW;                   // of stage ks+1
+                    constexpr int base_prev = (((ph + PERIOD - 1) % PERIOD) * L) % RW;   // of stage ks-1
+                    static_for<QS>([&](auto h_c) {
+                        constexpr int h = decltype(h_c)::value;
+                        constexpr int set = h & 1;
+                        static_for<C_::SLOTS>([&](auto q_c) {
+                            constexpr int q = decltype(q_c)::value;
+                            mfma_acc<(q % MB) * NB + q / MB>(fr[set][MB + q / MB], fr[set][q % MB]);
+                            static_for<C_::QUOTA>([&](auto k_c) {
+                                constexpr int o = q * C_::QUOTA + decltype(k_c)::value;
+                                if constexpr (h == QS - 2) {
+                                    // the quarter before the barrier issues no loads: its fragment reads go first, so
+                                    // that they are back when the wave reaches the barrier
+                                    if constexpr (o < C_::F)
+                                        read_frag(std::integral_constant<int, o>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
+                                } else if constexpr (o < LQ) {
+                                    // quarter 3 starts the batch released by this stage's barrier (j-th load of the
+                                    // batch: stream index ks*L + RW + j); quarters 0 and 1 finish the batch released by
+                                    // the previous stage's barrier
+                                    if constexpr (h == QS - 1) {
+                                        constexpr int j = o;
+                                        if constexpr (j < L)
+                                            load_unit(std::integral_constant<int, (RW + j) % L>{},
+                                                           std::integral_constant<int, (base_cur + j) % RW>{},
+                                                           min(ks + (RW + j) / L, KS - 1));
+                                    } else {
+                                        constexpr int j = (h + 1) * LQ + o;
+                                        if constexpr (j < L)
+                                            load_unit(std::integral_constant<int, (RW + j) % L>{},
+                                                           std::integral_constant<int, (base_prev + j) % RW>{},
+                                                           min(ks - 1 + (RW + j) / L, KS - 1));
+                                    }
+                                } else if constexpr (o - LQ < C_::F) {
+                                    constexpr int f = o - LQ;
+                                    if constexpr (h < QS - 1)
+                                        read_frag(std::integral_constant<int, f>{}, std::integral_constant<int, base_cur>{}, h + 1, 1 - set);
+                                    else
+                                        read_frag(std::integral_constant<int, f>{}, std::integral_constant<int, base_next>{}, 0, 1 - set);
+                                }
+                            });
+                        });
+                        if constexpr (h == QS - 2) {
+                            // stage ks+1 has landed for this wave (all but the RW - 2L youngest loads are back), its own
+                            // fragment reads of this stage are back; after the barrier that holds for all waves
+                            __builtin_amdgcn_s_waitcnt(vmcnt_imm(RW - 2 * L) & ~(0xF << 8));     // and lgkmcnt(0)
+                            __builtin_amdgcn_s_barrier();
+                        }
+                    });
+                    if (ks + 1 >= KS) done = true;
+                });
+                if (done) break;
+            }
         }
 
         // ---- epilogue.  Accumulator block (i, j) is the transposed block: lane l holds output row
@@ -418,17 +590,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                     constexpr int cpr = BN * esz / 16;                // 16-byte chunks per row
                     constexpr int iters = (32 * cpr + 63) / 64;       // chunk c = lane + 64*it: row c / cpr, chunk c % cpr
                     unsigned char* stage = lds + wave * 32 * pitch;
-                    unsigned char* wr = stage + (lane_e & 31) * pitch + 4 * (lane_e >> 5) * esz;
+                    unsigned char* wr = MF == 16 ? stage + (lane_e & 15) * pitch + 4 * (lane_e >> 4) * esz
+                                                 : stage + (lane_e & 31) * pitch + 4 * (lane_e >> 5) * esz;
                     const int r_lane = lane_e / cpr, cc_lane = lane_e - r_lane * cpr;
                     static_for<MB>([&](auto i_c) {
                         constexpr int i = decltype(i_c)::value;
-                        static_for<NB * 4>([&](auto jq_c) {
-                            constexpr int j = decltype(jq_c)::value / 4, qd = decltype(jq_c)::value % 4;
-                            constexpr int r0 = (i * NB + j) * 16 + qd * 4;
-                            const float x0 = acc_read<r0>(), x1 = acc_read<r0 + 1>(), x2 = acc_read<r0 + 2>(),
-                                        x3 = acc_read<r0 + 3>();
-                            *(Tx4*)(wr + (j * 32 + qd * 8) * esz) = Tx4{(T)x0, (T)x1, (T)x2, (T)x3};
-                        });
+                        if constexpr (MF == 16) {
+                            // 16x16 block (ib, j) of the pass: lane l holds row 16 ib + l%16, columns 16 j + 4 (l/16) + 0..3
+                            static_for<2 * C_::NB16>([&](auto bj_c) {
+                                constexpr int ib = decltype(bj_c)::value / C_::NB16, j = decltype(bj_c)::value % C_::NB16;
+                                constexpr int r0 = ((2 * i + ib) * C_::NB16 + j) * 4;
+                                const float x0 = acc_read<r0>(), x1 = acc_read<r0 + 1>(), x2 = acc_read<r0 + 2>(),
+                                            x3 = acc_read<r0 + 3>();
+                                *(Tx4*)(wr + ib * 16 * pitch + j * 16 * esz) = Tx4{(T)x0, (T)x1, (T)x2, (T)x3};
+                            });
+                        } else {
+                            static_for<NB * 4>([&](auto jq_c) {
+                                constexpr int j = decltype(jq_c)::value / 4, qd = decltype(jq_c)::value % 4;
+                                constexpr int r0 = (i * NB + j) * 16 + qd * 4;
+                                const float x0 = acc_read<r0>(), x1 = acc_read<r0 + 1>(), x2 = acc_read<r0 + 2>(),
+                                            x3 = acc_read<r0 + 3>();
+                                *(Tx4*)(wr + (j * 32 + qd * 8) * esz) = Tx4{(T)x0, (T)x1, (T)x2, (T)x3};
+                            });
+                        }
                         // the same wave wrote and reads: LDS keeps a wave's operations in order.  GRP chunks at a
                         // time: their LDS reads first (independent registers), then their stores.
                         const int row0 = row_w + i * 32;
@@ -507,6 +691,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                     });
                 } else {
                     // edge tiles and unaligned outputs: one element at a time, constant offsets from one row pointer
+                    if constexpr (MF == 16) {
+                        static_for<C_::MB16>([&](auto i_c) {
+                            constexpr int i = decltype(i_c)::value;
+                            char* dst = row_ptr(row_w + i * 16 + (lane_e & 15), esz);
+                            const int col0 = n0 + 4 * (lane_e >> 4);
+                            T* q = (T*)dst + 4 * (lane_e >> 4);
+                            static_for<C_::NB16 * 4>([&](auto jv_c) {
+                                constexpr int j = decltype(jv_c)::value / 4, v = decltype(jv_c)::value % 4;
+                                constexpr int off = j * 16 + v;
+                                const float x = acc_read<(i * C_::NB16 + j) * 4 + v>();
+                                if (dst && col0 + off < p.N) q[off] = (T)x;
+                            });
+                        });
+                    } else {
                     static_for<MB>([&](auto i_c) {
                         constexpr int i = decltype(i_c)::value;
                         char* dst = row_ptr(row_w + i * 32 + (lane_e & 31), esz);
@@ -519,6 +717,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                             if (dst && col0 + off < p.N) q[off] = (T)x;
                         });
                     });
+                    }
                 }
             };
             if (p.c_is_f32) epilogue(float{}); else epilogue(__bf16{});
@@ -570,39 +769,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
 #endif
 }
 
-template <int BM, int BN, bool GROUPED>
+template <int BM, int BN, bool GROUPED, int MF>
 static hipError_t launch_cfg(const GemmParams& p, int grid, hipStream_t stream)
 {
     using C_ = Cfg<BM, BN>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<BM, BN, GROUPED>,
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<BM, BN, GROUPED, MF>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C_::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, GROUPED>), dim3(grid), dim3(256), C_::LDS_BYTES, stream, p);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, GROUPED, MF>), dim3(grid), dim3(256), C_::LDS_BYTES, stream, p);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(const GemmParams& p, int cfg, int grid, hipStream_t stream)
-{
-    switch (cfg) {
-        case TILE_256x224: return launch_cfg<256, 224, false>(p, grid, stream);
-        case TILE_256x256: return launch_cfg<256, 256, false>(p, grid, stream);
-        case TILE_128x256: return launch_cfg<128, 256, false>(p, grid, stream);
-        default: return launch_cfg<128, 128, false>(p, grid, stream);
-    }
-}
-
-hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream_t stream)
-{
-    switch (cfg) {
-        case TILE_256x224: return launch_cfg<256, 224, true>(p, grid, stream);
-        case TILE_256x256: return launch_cfg<256, 256, true>(p, grid, stream);
-        case TILE_128x256: return launch_cfg<128, 256, true>(p, grid, stream);
-        default: return launch_cfg<128, 128, true>(p, grid, stream);
-    }
-}
-
 }  // namespace agg
+
+// One translation unit per tile configuration instantiates the plain and the grouped kernel of that configuration
+// (gemm_inst_*.hip), so that they compile side by side.
+#define AGG_GEMM_INSTANCE(BM, BN, MF)                                                                        \
+    namespace agg {                                                                                          \
+    hipError_t launch_gemm_##BM##x##BN##_mf##MF(const GemmParams& p, bool grouped, int grid, hipStream_t s)  \
+    {                                                                                                        \
+        return grouped ? launch_cfg<BM, BN, true, MF>(p, grid, s) : launch_cfg<BM, BN, false, MF>(p, grid, s); \
+    }                                                                                                        \
+    }

@@ -62,7 +62,7 @@ def test_tiny_bit_identical_over_all_arrival_orders_and_launch_orders():
         run.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", list(range(8)))
 def test_integer_inputs_are_exact(tile):
     # entries in {-2..2}: every partial sum is an integer below 2^24, so fp32 accumulation is exact
     inp = wl.make_ag_gemm(wl.AG_RAGGED, a_dist=("int", 2), b_dist=("int", 2))
@@ -87,7 +87,7 @@ def test_identity_b_returns_gathered_a_bit_exactly():
         run.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", list(range(8)))
 @pytest.mark.parametrize("chunks", [1, 4])
 def test_ragged_shape_f32_and_bf16(tile, chunks):
     inp = wl.make_ag_gemm(wl.AG_RAGGED)         # M=600, N=328, K=320: ragged against every tile shape
@@ -345,7 +345,7 @@ def test_world_of_one_is_a_plain_gemm():
     assert np.array_equal(want, oracle.ag_gemm(inp.shards, inp.B_kn, 0))
     run = AgGemmRun(inp, 0)
     try:
-        for tile in (0, 1, 2, 3):
+        for tile in range(8):
             check_f32(run.run(tile=tile).cpu().numpy(), want, sh.K)
     finally:
         run.close()
@@ -427,7 +427,7 @@ def test_short_and_odd_k_ranges(K):
     want = oracle.ag_gemm(inp.shards, inp.B_kn, 1)
     run = AgGemmRun(inp, 1)
     try:
-        for tile in (0, 1, 2, 3):
+        for tile in range(8):
             C = run.run(tile=tile).cpu().numpy()
             assert np.array_equal(C.astype(np.float64), want), (K, tile)      # integer inputs: exact
     finally:

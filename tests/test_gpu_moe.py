@@ -70,7 +70,7 @@ def _check_y(Y, want, K):
 
 
 @pytest.mark.parametrize("rank", [0, 2])
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", list(range(8)))
 def test_moe_tiny_against_oracle(rank, tile):
     sh = wl.MOE_TINY
     inp = wl.make_moe(sh)

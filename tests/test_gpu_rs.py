@@ -235,7 +235,7 @@ def _gemm_rs_case(shape, rank, rows_own, rows_other, tile=None, with_other=True,
 
 
 @pytest.mark.parametrize("rank", [0, 1, 3])
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", list(range(8)))
 def test_gemm_rs_tiny(rank, tile):
     sh = wl.RS_TINY
     rows_other = [r for r in range(sh.M) if not (rank * sh.Ms <= r < (rank + 1) * sh.Ms)]
@@ -325,7 +325,7 @@ def _all_ranks_gemm_rs(shape, reducers_first, tile=None, rows=None, chunks=1):
             rr.close()
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", list(range(8)))
 def test_all_ranks_on_one_gpu_tiny(tile):
     # The GEMMs are launched before the reducers: eight streams share the device's few hardware queues, and a GEMM
     # queued behind a reducer that waits for that very GEMM's signal could not start.
