@@ -337,9 +337,11 @@ int moe_rs(agg_ctx* ctx, int Ttok, int topk, int E, int N, int Klocal,
            const float* const* slots, float* Z_other, void* R, int ldr, int r_dtype,
            void* gemm_stream, void* reduce_stream);
 
-/* Tile shape of the GEMM kernels: -1 = chosen from the problem shape (default), 0 = 256x224, 1 = 128x128,
- * 2 = 256x256, 3 = 128x256.  A tuning knob (Section 3.8); every shape gives the same result (the sum over K runs in
- * the same order in all of them). */
+/* Tile configuration of the GEMM kernels: -1 = chosen from the problem shape (default); bits 0-1 = tile shape
+ * (0 = 256x224, 1 = 128x128, 2 = 256x256, 3 = 128x256), bit 2 = MFMA form of the main loop (0: 32x32x16, 4: 16x16x32,
+ * what the automatic choice takes).  A tuning knob (Section 3.8).  All shapes of one MFMA form give the same bits
+ * (the sum over K runs in the same order in all of them); the two forms group the sum over K differently (16 or 32
+ * terms per instruction) and may differ in the last bits, both within the tolerance. */
 int agg_set_tile_config(agg_ctx* ctx, int tile_config);
 
 /*

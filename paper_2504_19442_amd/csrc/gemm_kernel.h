@@ -40,6 +40,8 @@ namespace agg {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef __attribute__((address_space(3))) const bf16x8 lds_frag;
 
 // Raw buffer descriptor over `bytes` bytes at p: loads whose per-lane offset is >= bytes return zero, which
 // is how rows past the edge of A or B are masked.  0x00020000 = 32-bit data format, no swizzle (gfx9 family).
@@ -132,19 +134,24 @@ struct Cfg {
     static constexpr int MB16 = TM / 16;
     static constexpr int NB16 = BN / 16;
     static constexpr int DLY = 3;                // the stage's barrier sits after group DLY - 1 of the second half-step
-    static constexpr int LH1 = (NB16 - DLY < L) ? NB16 - DLY : L;   // loads issued in the rest of that half-step, one per group
-    static constexpr int LH0 = L - LH1;          // the others: in the first groups of the next stage's first half-step
-    static constexpr int P0 = RW - L + LH1;      // loads issued by the prologue
-    static_assert(LH0 <= NB16 && P0 >= L && P0 <= 63, "load schedule of the 16x16x32 loop");
-    static_assert(DLY + MB16 <= NB16, "the reads of the next A fragments fit between the barrier and the end of the half-step");
-    struct Op { int type, idx; };                // 0 none, 1 read B fragment idx, 2 read A fragment idx, 3 global->LDS load idx
     static constexpr int NS = NB16 * MB16;       // MFMA slots per half-step: slot s = group s / MB16, row block s % MB16
     static constexpr int SB = DLY * MB16 - 1;    // the barrier follows the MFMA of this slot (second half-step)
+    // The L loads that a barrier releases are issued one every PACE slots from the barrier on, through the rest of that
+    // half-step and the next stage's first half-step: evenly, because the four waves share one path into LDS (a load
+    // of one wave occupies it for 16 cycles, one MFMA slot) and bunched loads make the waves queue up at issue.
+    static constexpr int PACE = (2 * NS - SB - 1) / L > 0 ? (2 * NS - SB - 1) / L : 1;
+    static constexpr int LH1_ = (NS - SB + PACE - 1) / PACE;
+    static constexpr int LH1 = LH1_ < L ? LH1_ : L;   // loads issued in the rest of the second half-step
+    static constexpr int LH0 = L - LH1;          // the others: in the next stage's first half-step
+    static constexpr int P0 = RW - L + LH1;      // loads issued by the prologue
+    static_assert(SB + (L - 1) * PACE < 2 * NS && P0 >= L && P0 <= 63, "load schedule of the 16x16x32 loop");
+    static_assert(DLY + MB16 <= NB16, "the reads of the next A fragments fit between the barrier and the end of the half-step");
+    struct Op { int type, idx; };                // 0 none, 1 read B fragment idx, 2 read A fragment idx, 3 global->LDS load idx
     static constexpr int PER_SLOT = 3;
     struct Slots { Op op[NS][PER_SLOT]; bool complete; };
     // The memory operations of half-step h, placed behind the MFMA slots.  Each has an earliest slot: the refill of B
     // register set j after the last MFMA of group j (and, in the second half-step, not before the barrier); the reads
-    // of the next A fragments one per group from group DLY on; the global->LDS loads one per group, from the barrier on.  They are
+    // of the next A fragments one per group from group DLY on; the global->LDS loads one every PACE slots, from the barrier on.  They are
     // taken in that order, one per slot, two when three or more are ready; the last slot takes whatever is left.
     static constexpr Slots make_slots(int h)
     {
@@ -157,8 +164,8 @@ struct Cfg {
             ops[n] = Op{1, j}; early[n++] = e;
         }
         for (int ia = 0; ia < MB16; ++ia) { ops[n] = Op{2, ia}; early[n++] = (DLY + ia) * MB16; }
-        if (h == 1) for (int jj = 0; jj < LH1; ++jj) { ops[n] = Op{3, jj}; early[n++] = SB + jj * MB16; }
-        else for (int j = 0; j < LH0; ++j) { ops[n] = Op{3, LH1 + j}; early[n++] = j * MB16; }
+        if (h == 1) for (int jj = 0; jj < LH1; ++jj) { ops[n] = Op{3, jj}; early[n++] = SB + jj * PACE; }
+        else for (int jj = LH1; jj < L; ++jj) { ops[n] = Op{3, jj}; early[n++] = SB + jj * PACE - NS; }
         for (int a = 1; a < n; ++a)                      // stable insertion sort by earliest slot
             for (int b = a; b > 0 && early[b - 1] > early[b]; --b) {
                 const Op to = ops[b]; ops[b] = ops[b - 1]; ops[b - 1] = to;
@@ -217,6 +224,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
 #pragma unroll
         for (int h = 0; h < QS; ++h)
             fr_off[h] = (lane & 31) * ROW_BYTES + (((2 * h + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+    }
+
+    // LDS addresses as numbers: of the ring's start, and of this wave's quarter of ring position 0
+    const unsigned lds_u = (unsigned)(unsigned long)(lds_byte*)LDS_PTR(lds);
+    unsigned lds_wave = lds_u + wave * 1024;
+    // MF = 16: a B fragment read is base + immediate; the immediate holds 16 bits, the ring is larger, so there are
+    // three bases per half-step (ring offsets 0, 64 KiB, 128 KiB), refreshed once per stage so that they stay registers
+    unsigned frb[2][3];
+    if constexpr (MF == 16) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int k = 0; k < 3; ++k) frb[h][k] = lds_u + fr_off[h] + k * 65536;
     }
 
     const int KS = p.K / BK;             // stages
@@ -339,12 +359,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
         }
 
         // one global->LDS load: the i-th load of stage ks of this wave, into ring position pos (compile-time)
+        // (the LDS address of this wave's quarter of ring position 0 is kept as a number the compiler cannot see
+        // through: each load then takes one scalar add for its destination, instead of one live scalar register per
+        // ring position)
         auto load_unit = [&](auto i_c, auto pos_c, int ks) {
             constexpr int i = decltype(i_c)::value, pos = decltype(pos_c)::value;
             constexpr bool is_a = 4 * i < C_::A_UNITS;      // the same for all four waves
-            unsigned char* dst = lds + pos * 4096 + wave * 1024;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, LDS_PTR(dst), 16, ld_off[i],
-                                                     ks * ROW_BYTES, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? a_rsrc : b_rsrc, (lds_byte*)(unsigned long)(lds_wave + pos * 4096),
+                                                     16, ld_off[i], ks * ROW_BYTES, 0, 0);
         };
 
         static_for<C_::ACC>([&](auto r) { acc_zero<decltype(r)::value>(); });
@@ -364,12 +386,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                 const int rb = wave * MB16 + i;                  // wave-uniform
                 int pos = base + (rb >> 1);
                 if (pos >= RW) pos -= RW;
-                fa[set][i] = *(const bf16x8*)(lds + pos * 4096 + (rb & 1) * 2048 + fr_off[h]);
+                fa[set][i] = *(lds_frag*)(unsigned long)(frb[h][0] + (unsigned)(pos * 4096 + (rb & 1) * 2048));
             };
             auto read_b = [&](auto j_c, auto base_c, auto h_c) {
                 constexpr int j = decltype(j_c)::value, base = decltype(base_c)::value, h = decltype(h_c)::value;
                 constexpr int pos = (base + C_::A_UNITS / 4 + j / 2) % RW;
-                fb[j] = *(const bf16x8*)(lds + pos * 4096 + (j & 1) * 2048 + fr_off[h]);
+                constexpr int off = pos * 4096 + (j & 1) * 2048;
+                fb[j] = *(lds_frag*)(unsigned long)(frb[h][off >> 16] + (off & 0xFFFF));
             };
 
             // ---- prologue: the first P0 loads of the stream (stage 0, stage 1, the head of stage 2 ...); the main loop's
@@ -409,6 +432,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                     constexpr int base_cur = (ph * L) % RW;                              // ring base of stage ks
                     constexpr int base_next = ((ph + 1) * L) % RW;                       // of stage ks+1
                     constexpr int base_prev = (((ph + PERIOD - 1) % PERIOD) * L) % RW;   // of stage ks-1
+                    asm volatile("" : "+s"(lds_wave), "+v"(frb[0][0]), "+v"(frb[0][1]), "+v"(frb[0][2]), "+v"(frb[1][0]),
+                                 "+v"(frb[1][1]), "+v"(frb[1][2]));
                     static_for<2>([&](auto h_c) {
                         constexpr int h = decltype(h_c)::value;
                         // where the next half-step's fragments are

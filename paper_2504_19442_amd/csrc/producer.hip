@@ -4,9 +4,7 @@
 // registers, so its waves fit beside the consumer's on any CU (Section 3.8, resource partition).
 #include "agg_internal.h"
 
-#ifndef AGG_PROD_LOAD_AUX
 #define AGG_PROD_LOAD_AUX 2          // cache policy bits of the copy's loads: 2 = nt (streaming)
-#endif
 
 namespace agg {
 
