@@ -136,6 +136,7 @@ def main() -> int:
         Wt = (torch.randn((ms.E, ms.N, ms.K), device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
         ids = torch.rand((ms.T, ms.E), device="cuda", generator=gen).argsort(dim=1)[:, : ms.topk].to(torch.int32).contiguous()
         mctx = agg.symm_alloc(ms.W, 0, ms.tokens_per_rank * ms.K * 2, ms.W * args.chunks)
+        agg.agg_reserve_moe(mctx, ms.T, ms.topk, ms.E, ms.N)
         mp, mc = mctx.streams()
         mctx.set_tile_config(args.tile)
         Pm = ms.T * ms.topk
@@ -589,6 +590,7 @@ def main() -> int:
         keys = torch.rand((ms.T, ms.E), device="cuda", generator=gen)
         ids = keys.argsort(dim=1)[:, : ms.topk].to(torch.int32).contiguous()
         mctx = agg.symm_alloc(ms.W, 0, ms.tokens_per_rank * ms.K * 2, ms.W * args.chunks)
+        agg.agg_reserve_moe(mctx, ms.T, ms.topk, ms.E, ms.N)
         mp, mc = mctx.streams()
         mps, mcs = torch.cuda.ExternalStream(mp), torch.cuda.ExternalStream(mc)
         Pm = ms.T * ms.topk
@@ -629,6 +631,7 @@ def main() -> int:
         sl2 = [torch.randn((mr.tokens_per_rank, mr.N), device="cuda", dtype=torch.float32) for _ in range(mr.W)]
         R2 = torch.empty((mr.tokens_per_rank, mr.N), device="cuda", dtype=torch.float32)
         qctx = agg.symm_alloc(mr.W, 0, 16, mr.W)
+        agg.agg_reserve_moe(qctx, mr.T, mr.topk, mr.E, mr.N)
         qp, qc = qctx.streams()
 
         def step_moe_rs():

@@ -13,8 +13,8 @@
  * effect when it fails; agg_strerror names a code.  Functions are not thread-safe
  * on one context; different contexts are independent.  A context carries one set of
  * arrival counters, slice counters and tile tables: two producers, two gemm_rs /
- * gemm_rs_scatter or two ag_moe_gemm launches of ONE context must not be in flight at
- * the same time (order them on a stream or with events, or use a context each).
+ * gemm_rs_scatter, two ag_moe_gemm launches or two GEMMs with an AGG_B_KN operand of ONE context must not
+ * be in flight at the same time (order them on a stream or with events, or use a context each).
  *
  * Vocabulary (the paper's, Section 2.1 and Algorithms 1-3): W = WORLD_SIZE,
  * rank = RANK, T = symmetric buffer, S = signal array, L = a rank's local shard.
@@ -40,14 +40,17 @@ enum {
     AGG_ERR_TIMEOUT = -5,           /* a kernel gave up waiting for a signal (reported by agg_status) */
     AGG_ERR_NOMEM = -6,
     AGG_ERR_NOT_FOUND = -7,         /* the table of tuned configurations has no entry for the problem */
-    AGG_ERR_IO = -8                 /* a file could not be opened, read or written */
+    AGG_ERR_IO = -8,                /* a file could not be opened, read or written */
+    AGG_ERR_NOT_RESERVED = -9       /* a workspace the call needs has not been reserved, or is too small */
 };
 
 enum { AGG_BF16 = 0, AGG_F32 = 1 };          /* element type of an output matrix */
 enum { AGG_B_NK = 0,                         /* B stored [N][K], K contiguous (weight layout of a linear layer): read in place */
        AGG_B_KN = 1 };                       /* B stored [K][N], N contiguous: transposed into a buffer of the context
                                                 on the GEMM's stream before every GEMM (one more pass over B; the
-                                                first such call allocates the buffer and synchronises); ldb >= N */
+                                                buffer is sized by agg_reserve_b_kn beforehand; calls with this
+                                                layout on one context share it, so they must be ordered on one
+                                                stream or with events); ldb >= N */
 enum { AGG_PRODUCER_KERNEL = 0,              /* copy kernel on a few CUs, release-stores the signals */
        AGG_PRODUCER_SDMA = 1,               /* copy engine (no compute units) + one 4-byte copy per signal */
        AGG_PRODUCER_LINKS = 2,              /* full mesh: every peer's shard on a "link" of its own, all at once, chunk by chunk */
@@ -102,9 +105,9 @@ int signal_reset(agg_ctx* ctx, void* stream);
  * (an event from the reset's stream to the producer's and the consumer's), and a whole run -- reset, arrival, gated
  * GEMM, join -- can be recorded into a HIP graph by stream capture and replayed: every replay is a run with a fresh
  * epoch.  (With the epoch on the host a replay would compare the signals with the epoch of the recording, which the
- * first run has already reached.)  Nothing this library enqueues for a run is a memset or an allocation; the first
- * ag_gemm of a tile shape sets a function attribute and ag_moe_gemm / AGG_B_KN allocate on first use, so run once
- * before recording.  In this mode gemm_rs and moe_rs order their reducer behind the whole GEMM with an event (a stream
+ * first run has already reached.)  Nothing this library enqueues for a run is a memset or an allocation (workspaces
+ * are sized beforehand by the agg_reserve_* calls); the first launch of a tile configuration sets a function
+ * attribute, so run once before recording.  In this mode gemm_rs and moe_rs order their reducer behind the whole GEMM with an event (a stream
  * wait on memory compares with a value fixed at enqueue time).  symm_epoch keeps counting the host's resets and does
  * not see replays.  Synchronises the device.
  */
@@ -260,13 +263,24 @@ int gemm_rs_scatter(agg_ctx* ctx, int M, int N, int Klocal,
  * weights and topk_ids 16-byte aligned, ldy >= N.  Ids outside [0, E) are skipped: their pairs appear nowhere and
  * sorted_expert_offsets[E] is then smaller than Ttok * topk.  Rows of Y past sorted_expert_offsets[E] are not
  * written.  Routing and GEMM run on `stream`; routing does not depend on T and runs before any signal is awaited.
- * The first call (and any call with a larger problem) allocates the context's tile table and synchronises the
- * device; later calls allocate nothing.
+ * The call allocates nothing and does not synchronise: the tile table it builds lives in a workspace of the context
+ * that agg_reserve_moe sizes beforehand (AGG_ERR_NOT_RESERVED otherwise).
  */
 int ag_moe_gemm(agg_ctx* ctx, int Ttok, int topk, int E, int N, int K,
                 const int32_t* topk_ids, const void* weights,
                 int32_t* sorted_token, int32_t* sorted_expert_offsets,
                 void* Y, int ldy, int y_dtype, void* stream);
+
+/*
+ * Workspaces of a context, sized ahead of the calls that use them; these two are the only calls besides symm_alloc that
+ * allocate device memory (they synchronise the device; they only ever grow a workspace).  No GEMM, MoE or reducer call
+ * allocates or synchronises: one that finds its workspace missing or too small returns AGG_ERR_NOT_RESERVED.
+ *   agg_reserve_b_kn: the [N][K] copy of a B operand given as AGG_B_KN (ag_gemm, gemm_rs, gemm_rs_scatter).
+ *   agg_reserve_moe : the tile count and tile table of the grouped GEMM (ag_moe_gemm, moe_rs) for problems of up to
+ *                     Ttok * topk pairs, E experts and N columns, whatever tile configuration is chosen later.
+ */
+int agg_reserve_b_kn(agg_ctx* ctx, int N, int K);
+int agg_reserve_moe(agg_ctx* ctx, int Ttok, int topk, int E, int N);
 
 /*
  * Let ag_gemm read this rank's own shard from `local_shard` (DEVICE pointer to L_rank, [Ms][K] bf16, 16-byte aligned,

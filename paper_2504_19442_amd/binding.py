@@ -12,10 +12,10 @@ import os
 
 __all__ = [
     "AggError", "Ctx", "symm_alloc", "signal_reset", "signal_set", "ag_producer_emulate", "ag_gemm",
-    "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "moe_rs", "agg_autotune_ag_gemm", "agg_mfma_ceiling", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
+    "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "agg_reserve_b_kn", "agg_reserve_moe", "moe_rs", "agg_autotune_ag_gemm", "agg_mfma_ceiling", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
     "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL", "PRODUCER_LOCAL_LAST",
     "ORDER_ROTATED", "ORDER_SUBCHUNK", "SIGNAL_STRIDE",
-    "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM", "ERR_NOT_FOUND", "ERR_IO",
+    "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM", "ERR_NOT_FOUND", "ERR_IO", "ERR_NOT_RESERVED",
     "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load",
     "agg_tune_table_apply", "TuneResult",
     "EXPORTS",
@@ -27,13 +27,13 @@ PRODUCER_KERNEL, PRODUCER_SDMA, PRODUCER_LINKS, PRODUCER_SKIP_LOCAL, PRODUCER_LO
 ORDER_ROTATED, ORDER_SUBCHUNK = 0, 1
 SIGNAL_STRIDE = 32
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT, ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
-ERR_NOT_FOUND, ERR_IO = -7, -8
+ERR_NOT_FOUND, ERR_IO, ERR_NOT_RESERVED = -7, -8, -9
 
 # every symbol include/agg.h declares
 EXPORTS = [
     "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
     "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs", "gemm_rs_scatter", "agg_autotune_ag_gemm", "agg_mfma_ceiling",
-    "ag_moe_gemm", "moe_rs", "agg_set_tile_config", "agg_set_device_epoch", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load", "agg_tune_table_apply", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
+    "ag_moe_gemm", "agg_reserve_b_kn", "agg_reserve_moe", "moe_rs", "agg_set_tile_config", "agg_set_device_epoch", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load", "agg_tune_table_apply", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
 ]
 
 
@@ -90,6 +90,8 @@ def _lib() -> C.CDLL:
         L.agg_mfma_ceiling.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
         L.moe_rs.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(vp), vp, vp, i32, i32, vp, vp]
         L.ag_moe_gemm.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32, vp]
+        L.agg_reserve_b_kn.argtypes = [vp, i32, i32]
+        L.agg_reserve_moe.argtypes = [vp, i32, i32, i32, i32]
         L.agg_strerror.argtypes = [i32]
         L.agg_strerror.restype = C.c_char_p
         L.agg_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32)]
@@ -333,6 +335,14 @@ def ag_moe_gemm(ctx: Ctx, Ttok: int, topk: int, E: int, N: int, K: int, topk_ids
                 sorted_expert_offsets, Y, ldy: int, y_dtype: int, stream=None) -> None:
     _check(_lib().ag_moe_gemm(ctx.handle, Ttok, topk, E, N, K, _ptr(topk_ids), _ptr(weights), _ptr(sorted_token),
                               _ptr(sorted_expert_offsets), _ptr(Y), ldy, y_dtype, _stream(stream)), "ag_moe_gemm")
+
+
+def agg_reserve_b_kn(ctx: Ctx, N: int, K: int) -> None:
+    _check(_lib().agg_reserve_b_kn(ctx.handle, N, K), "agg_reserve_b_kn")
+
+
+def agg_reserve_moe(ctx: Ctx, Ttok: int, topk: int, E: int, N: int) -> None:
+    _check(_lib().agg_reserve_moe(ctx.handle, Ttok, topk, E, N), "agg_reserve_moe")
 
 
 def agg_device_info():

@@ -177,12 +177,11 @@ struct agg_ctx {
     const void* local_shard;  // see agg_set_local_shard
     double link_GBps;    // pace of a link of the full-mesh producer (0 = not paced)
     hipStream_t producer_stream, consumer_stream;
-    // grouped GEMM workspace (grown on demand by ag_moe_gemm)
-    int* moe_ws;          // counts[E] | tile_first[E+1] | n_tiles
-    int moe_ws_ints;
+    // grouped GEMM workspace (sized by agg_reserve_moe; no other call allocates it)
+    int* moe_ws;          // the tile count of the launch under way (one word)
     agg::MoeTile* moe_tab;
     int moe_tab_cap;
-    uint16_t* b_nk;       // [N][K] copy of a B that was given as [K][N] (grown on demand)
+    uint16_t* b_nk;       // [N][K] copy of a B that was given as [K][N] (sized by agg_reserve_b_kn)
     size_t b_nk_elems;
     int can_wait_value;  // the device supports stream waits on a memory word
     hipEvent_t gemm_done; // GEMM-RS: orders the reducer after the GEMM where it does not

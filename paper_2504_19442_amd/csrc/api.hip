@@ -86,8 +86,8 @@ int check_gemm_operands(int M, int N, int K, const void* B, int ldb, int b_layou
 }
 
 // The GEMM kernel reads B as [N][K].  A B given as [K][N] is transposed first, on the GEMM's stream, into a buffer
-// of the context (grown on demand: the first such call allocates and synchronises).  Callers whose weights do not
-// change should store them as [N][K] and save the pass (2 x N x K x 2 bytes of traffic per call).
+// of the context that agg_reserve_b_kn has sized beforehand: the call itself allocates nothing.  Callers whose
+// weights do not change should store them as [N][K] and save the pass (2 x N x K x 2 bytes of traffic per call).
 int resolve_b(agg_ctx* c, const void* B, int ldb, int b_layout, int N, int K, hipStream_t stream, const uint16_t** B_nk,
               long long* ld_nk)
 {
@@ -96,20 +96,16 @@ int resolve_b(agg_ctx* c, const void* B, int ldb, int b_layout, int N, int K, hi
         *ld_nk = ldb;
         return AGG_OK;
     }
-    const size_t need = (size_t)N * K;
-    if (c->b_nk_elems < need) {
-        HIP_TRY(hipDeviceSynchronize());
-        if (c->b_nk) (void)hipFree(c->b_nk);
-        c->b_nk = nullptr;
-        c->b_nk_elems = 0;
-        HIP_TRY(hipMalloc((void**)&c->b_nk, need * sizeof(uint16_t)));
-        c->b_nk_elems = need;
-    }
+    if (c->b_nk_elems < (size_t)N * K) return AGG_ERR_NOT_RESERVED;
     HIP_TRY(launch_transpose_kn((const uint16_t*)B, ldb, K, N, c->b_nk, stream));
     *B_nk = c->b_nk;
     *ld_nk = K;
     return AGG_OK;
 }
+
+// Upper bound of the grouped GEMM's tile table over all tile configurations: sum over experts of
+// ceil(rows / bm) <= P / bm + E, times the n-tiles, for the smallest tile (128 x 128).
+long long moe_table_bound(long long P, int E, int N) { return (P / 128 + E) * ((N + 127) / 128); }
 
 // The producer stream must run side by side with the consumer stream: streams that the runtime has put on one
 // hardware queue run their kernels one after the other.  Which queue a new stream gets cannot be asked for, so it
@@ -328,6 +324,40 @@ int agg_status(agg_ctx* c)
         HIP_TRY(hipMemset(c->err, 0, sizeof h));
         HIP_TRY(hipDeviceSynchronize());
         return AGG_ERR_TIMEOUT;
+    }
+    return AGG_OK;
+}
+
+int agg_reserve_b_kn(agg_ctx* c, int N, int K)
+{
+    if (!c || N < 0 || K < 0) return AGG_ERR_INVALID_ARG;
+    const size_t need = (size_t)N * K;
+    if (c->b_nk_elems >= need) return AGG_OK;
+    HIP_TRY(hipDeviceSynchronize());
+    if (c->b_nk) (void)hipFree(c->b_nk);
+    c->b_nk = nullptr;
+    c->b_nk_elems = 0;
+    HIP_TRY(hipMalloc((void**)&c->b_nk, need * sizeof(uint16_t)));
+    c->b_nk_elems = need;
+    return AGG_OK;
+}
+
+int agg_reserve_moe(agg_ctx* c, int Ttok, int topk, int E, int N)
+{
+    if (!c || Ttok < 0 || topk < 1 || E < 1 || E > 4096 || N < 0) return AGG_ERR_INVALID_ARG;
+    const long long cap = moe_table_bound((long long)Ttok * topk, E, N);
+    if (cap > (1ll << 28)) return AGG_ERR_UNSUPPORTED_SHAPE;
+    if (!c->moe_ws) {
+        HIP_TRY(hipDeviceSynchronize());
+        HIP_TRY(hipMalloc((void**)&c->moe_ws, 256));
+    }
+    if (c->moe_tab_cap < cap) {
+        HIP_TRY(hipDeviceSynchronize());
+        if (c->moe_tab) (void)hipFree(c->moe_tab);
+        c->moe_tab = nullptr;
+        c->moe_tab_cap = 0;
+        HIP_TRY(hipMalloc((void**)&c->moe_tab, (size_t)cap * sizeof(MoeTile)));
+        c->moe_tab_cap = (int)cap;
     }
     return AGG_OK;
 }
@@ -761,9 +791,11 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
 
 // Routing + grouped GEMM, shared by ag_moe_gemm (A = T, rows gathered by token, tiles gated by the signals) and moe_rs
 // (A = the routed rows themselves, nothing to wait for).
+// The tile count (one device word) and the tile table come from the caller of this function: the context's reserved
+// buffers, or the library's static scratch.
 static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* A,
                         bool gathered, const void* weights, int32_t* sorted_token, int32_t* seg_off, int32_t* pair_pos,
-                        void* Y, int ldy, int y_dtype, hipStream_t stream)
+                        void* Y, int ldy, int y_dtype, hipStream_t stream, int* n_tiles_word, MoeTile* tab, long long tab_cap)
 {
     const long long P = (long long)Ttok * topk;
     const unsigned long long a_bytes = (unsigned long long)(gathered ? Ttok : P) * K * 2;
@@ -796,30 +828,13 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     const int tiles_n = (N + t.bn - 1) / t.bn;
     const long long cap = (P / t.bm + E) * tiles_n;              // sum over experts of ceil(rows / bm) <= P / bm + E
     if (cap > (1ll << 28)) return AGG_ERR_UNSUPPORTED_SHAPE;
-    // workspace of the context, grown on demand (the only calls that allocate; they synchronise the device)
-    const int ws_ints = 2 * E + 2 + 32;
-    if (c->moe_ws_ints < ws_ints) {
-        HIP_TRY(hipDeviceSynchronize());
-        if (c->moe_ws) (void)hipFree(c->moe_ws);
-        c->moe_ws = nullptr;
-        c->moe_ws_ints = 0;
-        HIP_TRY(hipMalloc((void**)&c->moe_ws, (size_t)ws_ints * sizeof(int)));
-        c->moe_ws_ints = ws_ints;
-    }
-    if (c->moe_tab_cap < cap) {
-        HIP_TRY(hipDeviceSynchronize());
-        if (c->moe_tab) (void)hipFree(c->moe_tab);
-        c->moe_tab = nullptr;
-        c->moe_tab_cap = 0;
-        HIP_TRY(hipMalloc((void**)&c->moe_tab, (size_t)cap * sizeof(MoeTile)));
-        c->moe_tab_cap = (int)cap;
-    }
+    if (!n_tiles_word || !tab || tab_cap < cap) return AGG_ERR_NOT_RESERVED;
     MoeRouteArgs r{};
     r.topk_ids = topk_ids;
     r.P = (int)P;
     r.topk = topk;
     r.E = E;
-    r.n_tiles_dev = c->moe_ws + 2 * E + 1 + 16;
+    r.n_tiles_dev = n_tiles_word;
     r.seg_off = seg_off;
     r.sorted_token = sorted_token;
     r.pair_pos = pair_pos;
@@ -827,7 +842,7 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     r.tiles_n = tiles_n;
     r.rows_per_flag = gathered ? tpr / cps : 1;
     r.n_flags = c->n_signals;
-    r.tile_tab = c->moe_tab;
+    r.tile_tab = tab;
     r.tab_capacity = (int)cap;
     int rc = hip_fail(launch_moe_route(r, stream));
     if (rc != AGG_OK) return rc;
@@ -853,7 +868,7 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     p.wait_ticks = wait_ticks(c);
     p.err = c->err;
     p.row_index = gathered ? sorted_token : nullptr;      // nullptr: row p of the output reads row p of A
-    p.tile_tab = c->moe_tab;
+    p.tile_tab = tab;
     p.n_tiles_dev = r.n_tiles_dev;
     p.b_group_stride = (long long)N * K;
     p.a_bytes = (unsigned)a_bytes;
@@ -861,8 +876,9 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     return hip_fail(launch_gemm_grouped(p, cfg, grid, stream));
 }
 
-int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* weights,
-                int32_t* sorted_token, int32_t* sorted_expert_offsets, void* Y, int ldy, int y_dtype, void* stream)
+static int ag_moe_gemm_impl(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* weights,
+                            int32_t* sorted_token, int32_t* sorted_expert_offsets, void* Y, int ldy, int y_dtype, void* stream,
+                            int* n_tiles_word, MoeTile* tab, long long tab_cap)
 {
     if (!c || Ttok < 0 || topk < 1 || E < 1 || E > 4096 || N < 0 || K < 0) return AGG_ERR_INVALID_ARG;
     if (y_dtype != AGG_BF16 && y_dtype != AGG_F32) return AGG_ERR_INVALID_ARG;
@@ -876,7 +892,15 @@ int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32
     const int cps = c->n_signals / c->W;
     if (tpr % cps != 0) return AGG_ERR_UNSUPPORTED_SHAPE;
     return grouped_gemm(c, Ttok, topk, E, N, K, topk_ids, c->staging, true, weights, sorted_token, sorted_expert_offsets,
-                        nullptr, Y, ldy, y_dtype, (hipStream_t)stream);
+                        nullptr, Y, ldy, y_dtype, (hipStream_t)stream, n_tiles_word, tab, tab_cap);
+}
+
+int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* weights,
+                int32_t* sorted_token, int32_t* sorted_expert_offsets, void* Y, int ldy, int y_dtype, void* stream)
+{
+    if (!c) return AGG_ERR_INVALID_ARG;
+    return ag_moe_gemm_impl(c, Ttok, topk, E, N, K, topk_ids, weights, sorted_token, sorted_expert_offsets, Y, ldy, y_dtype,
+                            stream, c->moe_ws, c->moe_tab, c->moe_tab_cap);
 }
 
 int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, const void* weights2,
@@ -903,7 +927,7 @@ int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, 
 
     // 1. grouped GEMM on the routed rows (fp32 out)
     int rc = grouped_gemm(c, Ttok, topk, E, N, Kl, topk_ids, H, false, weights2, sorted_token, sorted_expert_offsets,
-                          pair_pos, Y, N, AGG_F32, (hipStream_t)gemm_stream);
+                          pair_pos, Y, N, AGG_F32, (hipStream_t)gemm_stream, c->moe_ws, c->moe_tab, c->moe_tab_cap);
     if (rc != AGG_OK) return rc;
     // 2. top-k reduction: this rank's tokens into its own slot (first), the others' into Z_other
     TopkReduceArgs t{};
@@ -963,6 +987,7 @@ const char* agg_strerror(int code)
         case AGG_ERR_NOMEM: return "out of memory";
         case AGG_ERR_NOT_FOUND: return "no such entry";
         case AGG_ERR_IO: return "file could not be read or written";
+        case AGG_ERR_NOT_RESERVED: return "workspace not reserved (agg_reserve_b_kn / agg_reserve_moe) or too small";
         default: return "unknown error";
     }
 }

@@ -440,7 +440,12 @@ def test_b_given_as_k_by_n_is_transposed_first_same_bits():
     run = AgGemmRun(inp, 2)
     try:
         base = run.run(tile=1).cpu().numpy()
-        from harness import dev_bf16
+        # the transposed copy lives in a workspace that no GEMM call allocates: without it the call is refused
+        Cx = torch.zeros((sh.M, sh.N), device="cuda", dtype=torch.float32)
+        with pytest.raises(agg.AggError) as e:
+            agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, run.B_nk, sh.N, agg.B_KN, Cx, sh.N, agg.F32, run.cons)
+        assert e.value.code == agg.ERR_NOT_RESERVED
+        agg.agg_reserve_b_kn(run.ctx, sh.N, sh.K)
         for pad in (0, 3):                                   # ldb = N and ldb = N + 3 (no alignment asked of this layout)
             host = np.zeros((sh.K, sh.N + pad), dtype=np.uint16)
             host[:, : sh.N] = inp.B_kn

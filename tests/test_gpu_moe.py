@@ -24,6 +24,7 @@ class MoeRun:
         self.Wd = dev_bf16(np.ascontiguousarray(np.transpose(inp.W_ekn, (0, 2, 1))))
         self.ids = torch.from_numpy(inp.topk_ids).cuda()
         self.ctx = agg.symm_alloc(sh.W, rank, sh.tokens_per_rank * sh.K * 2, sh.W * chunks_per_shard)
+        agg.agg_reserve_moe(self.ctx, sh.T, sh.topk, sh.E, sh.N)
         ps, cs = self.ctx.streams()
         self.prod, self.cons = torch.cuda.ExternalStream(ps), torch.cuda.ExternalStream(cs)
         self.staging = _tensor_from_ptr(self.ctx.staging, sh.T * sh.K)
@@ -216,4 +217,30 @@ def test_moe_full_size_whole_output():
                            consumer_first=False)
         assert torch.equal(Y, Y2)
     finally:
+        run.close()
+
+
+def test_moe_call_without_a_reserved_workspace_is_refused():
+    sh = wl.MOE_TINY
+    inp = wl.make_moe(sh)
+    run = MoeRun(inp, 0)
+    bare = agg.symm_alloc(sh.W, 0, sh.tokens_per_rank * sh.K * 2, sh.W)       # a context nobody reserved anything for
+    try:
+        P = sh.T * sh.topk
+        Y = torch.zeros((P, sh.N), device="cuda", dtype=torch.float32)
+        tok = torch.zeros((P,), device="cuda", dtype=torch.int32)
+        seg = torch.zeros((sh.E + 1,), device="cuda", dtype=torch.int32)
+        ids = torch.from_numpy(inp.topk_ids).cuda()
+        with pytest.raises(agg.AggError) as e:
+            agg.ag_moe_gemm(bare, sh.T, sh.topk, sh.E, sh.N, sh.K, ids, run.Wd, tok, seg, Y, sh.N, agg.F32, None)
+        assert e.value.code == agg.ERR_NOT_RESERVED
+        # a reserved context: the very first call (no warm call before it) goes through
+        run.run(out_dtype=agg.F32)
+        # a workspace reserved for a smaller problem is refused as well
+        agg.agg_reserve_moe(bare, sh.W, 1, 1, 16)
+        with pytest.raises(agg.AggError) as e:
+            agg.ag_moe_gemm(bare, sh.T, sh.topk, sh.E, sh.N, sh.K, ids, run.Wd, tok, seg, Y, sh.N, agg.F32, None)
+        assert e.value.code == agg.ERR_NOT_RESERVED
+    finally:
+        bare.free()
         run.close()

@@ -21,6 +21,7 @@ class MoeRsRun:
         self.gate = torch.from_numpy(inp.gate).cuda()
         self.chunks = chunks
         self.ctx = agg.symm_alloc(sh.W, rank, 16, sh.W * chunks)
+        agg.agg_reserve_moe(self.ctx, sh.T, sh.topk, sh.E, sh.N)
         self.ctx.set_rs_chunks(chunks)
         ps, cs = self.ctx.streams()
         self.prod, self.cons = torch.cuda.ExternalStream(ps), torch.cuda.ExternalStream(cs)

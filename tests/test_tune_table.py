@@ -33,7 +33,7 @@ def test_put_get_and_missing_entries():
     assert agg.agg_tune_table_get(8, 8192, 7168, 4096) is None
 
 
-@pytest.mark.parametrize("bad", [dict(tile=4), dict(tile=-1), dict(order=2), dict(wgs=-1), dict(wgs=5000), dict(ms=-1.0)])
+@pytest.mark.parametrize("bad", [dict(tile=8), dict(tile=-1), dict(order=2), dict(wgs=-1), dict(wgs=5000), dict(ms=-1.0)])
 def test_put_rejects_values_out_of_range(bad):
     with pytest.raises(agg.AggError) as e:
         agg.agg_tune_table_put(8, 64, 64, 64, _entry(**bad))
@@ -68,7 +68,7 @@ def test_save_load_round_trip_and_merge(tmp_path):
     "agg-tune-table 2\n",                                     # another version
     "agg-tune-table 1\n8 64 64 64 0 0 0 1\n",                 # a field missing
     "agg-tune-table 1\n8 64 64 64 0 0 0 1 0.5 7\n",           # a field too many
-    "agg-tune-table 1\n8 64 64 64 5 0 0 1 0.5\n",             # tile shape out of range
+    "agg-tune-table 1\n8 64 64 64 9 0 0 1 0.5\n",             # tile shape out of range
     "agg-tune-table 1\n8 64 64 64 0 0 0 1 nan\n",             # not a time
     "agg-tune-table 1\n8 64 64 x4 0 0 0 1 0.5\n",             # not a number
     "agg-tune-table 1\n8 64 64 64 0 0 0 1 0.5\n" + "9" * 400 + "\n",   # an overlong line
