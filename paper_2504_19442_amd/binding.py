@@ -12,7 +12,7 @@ import os
 
 __all__ = [
     "AggError", "Ctx", "symm_alloc", "signal_reset", "signal_set", "ag_producer_emulate", "ag_gemm",
-    "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "agg_reserve_b_kn", "agg_reserve_moe", "moe_rs", "agg_autotune_ag_gemm", "agg_mfma_ceiling", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
+    "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "ag_moe_gemm_static", "agg_reserve_b_kn", "agg_reserve_moe", "moe_rs", "agg_autotune_ag_gemm", "agg_mfma_ceiling", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
     "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL", "PRODUCER_LOCAL_LAST",
     "ORDER_ROTATED", "ORDER_SUBCHUNK", "SIGNAL_STRIDE",
     "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM", "ERR_NOT_FOUND", "ERR_IO", "ERR_NOT_RESERVED",
@@ -33,7 +33,7 @@ ERR_NOT_FOUND, ERR_IO, ERR_NOT_RESERVED = -7, -8, -9
 EXPORTS = [
     "symm_alloc", "symm_free", "symm_staging", "symm_signals", "symm_epoch", "symm_streams", "signal_reset", "signal_set",
     "agg_set_wait_limit_us", "agg_status", "ag_producer_emulate", "ag_gemm", "rs_reduce", "gemm_rs", "gemm_rs_scatter", "agg_autotune_ag_gemm", "agg_mfma_ceiling",
-    "ag_moe_gemm", "agg_reserve_b_kn", "agg_reserve_moe", "moe_rs", "agg_set_tile_config", "agg_set_device_epoch", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load", "agg_tune_table_apply", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
+    "ag_moe_gemm", "ag_moe_gemm_static", "agg_reserve_b_kn", "agg_reserve_moe", "moe_rs", "agg_set_tile_config", "agg_set_device_epoch", "agg_set_tile_order", "agg_set_rs_chunks", "agg_set_rs_own_slice_last", "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load", "agg_tune_table_apply", "agg_set_link_rate", "agg_set_local_shard", "agg_strerror", "agg_device_info",
 ]
 
 
@@ -90,6 +90,7 @@ def _lib() -> C.CDLL:
         L.agg_mfma_ceiling.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
         L.moe_rs.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, C.POINTER(vp), vp, vp, i32, i32, vp, vp]
         L.ag_moe_gemm.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32, vp]
+        L.ag_moe_gemm_static.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32, i32, vp]
         L.agg_reserve_b_kn.argtypes = [vp, i32, i32]
         L.agg_reserve_moe.argtypes = [vp, i32, i32, i32, i32]
         L.agg_strerror.argtypes = [i32]
@@ -335,6 +336,13 @@ def ag_moe_gemm(ctx: Ctx, Ttok: int, topk: int, E: int, N: int, K: int, topk_ids
                 sorted_expert_offsets, Y, ldy: int, y_dtype: int, stream=None) -> None:
     _check(_lib().ag_moe_gemm(ctx.handle, Ttok, topk, E, N, K, _ptr(topk_ids), _ptr(weights), _ptr(sorted_token),
                               _ptr(sorted_expert_offsets), _ptr(Y), ldy, y_dtype, _stream(stream)), "ag_moe_gemm")
+
+
+def ag_moe_gemm_static(ctx: Ctx, Ttok: int, topk: int, E: int, N: int, K: int, topk_ids, weights, sorted_token,
+                       sorted_expert_offsets, Y, ldy: int, y_dtype: int, stream=None) -> None:
+    _check(_lib().ag_moe_gemm_static(ctx.handle, Ttok, topk, E, N, K, _ptr(topk_ids), _ptr(weights), _ptr(sorted_token),
+                                     _ptr(sorted_expert_offsets), _ptr(Y), ldy, y_dtype, _stream(stream)),
+           "ag_moe_gemm_static")
 
 
 def agg_reserve_b_kn(ctx: Ctx, N: int, K: int) -> None:

@@ -103,6 +103,13 @@ int resolve_b(agg_ctx* c, const void* B, int ldb, int b_layout, int N, int K, hi
     return AGG_OK;
 }
 
+// ---- device memory that no call allocates: a fixed array in the library's image, one copy per GPU, used by
+// ag_moe_gemm_static for the grouped GEMM's tile count and tile table.  Host code never uses the array's name as an
+// address: the device address is looked up once per context (symm_alloc, with the context's device current).
+constexpr size_t kStaticScratchBytes = 1u << 20;
+constexpr size_t kStaticTabOffset = 256;                   // the tile count sits in the first line, the table after it
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 // Upper bound of the grouped GEMM's tile table over all tile configurations: sum over experts of
 // ceil(rows / bm) <= P / bm + E, times the n-tiles, for the smallest tile (128 x 128).
 long long moe_table_bound(long long P, int E, int N) { return (P / 128 + E) * ((N + 127) / 128); }
@@ -187,6 +194,7 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     if ((rc = hip_fail(hipStreamCreateWithFlags(&c->consumer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
     if ((rc = pick_concurrent_stream(c)) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipEventCreateWithFlags(&c->gemm_done, hipEventDisableTiming))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipGetSymbolAddress((void**)&c->static_scratch, HIP_SYMBOL(scratch)))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) goto fail;
     *out = c;
     return AGG_OK;
@@ -901,6 +909,18 @@ int ag_moe_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32
     if (!c) return AGG_ERR_INVALID_ARG;
     return ag_moe_gemm_impl(c, Ttok, topk, E, N, K, topk_ids, weights, sorted_token, sorted_expert_offsets, Y, ldy, y_dtype,
                             stream, c->moe_ws, c->moe_tab, c->moe_tab_cap);
+}
+
+int ag_moe_gemm_static(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* weights,
+                       int32_t* sorted_token, int32_t* sorted_expert_offsets, void* Y, int ldy, int y_dtype, void* stream)
+{
+    if (!c || !c->static_scratch) return AGG_ERR_INVALID_ARG;
+    // the table lives in the library's static device array: a problem whose table could exceed it is refused
+    const long long room = (long long)((kStaticScratchBytes - kStaticTabOffset) / sizeof(MoeTile));
+    if (Ttok > 0 && topk > 0 && E > 0 && N > 0 && moe_table_bound((long long)Ttok * topk, E, N) > room)
+        return AGG_ERR_UNSUPPORTED_SHAPE;
+    return ag_moe_gemm_impl(c, Ttok, topk, E, N, K, topk_ids, weights, sorted_token, sorted_expert_offsets, Y, ldy, y_dtype,
+                            stream, (int*)c->static_scratch, (MoeTile*)(c->static_scratch + kStaticTabOffset), room);
 }
 
 int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, const void* weights2,
