@@ -54,15 +54,6 @@ struct GemmParams {
     const int* n_tiles_dev;       // number of table entries (device word)
     long long b_group_stride;     // elements between the B matrices of consecutive groups (experts)
     unsigned a_bytes;             // size of A in bytes (bound of the gather)
-    // MoE + ReduceScatter with the top-k reduction in the epilogue (row_scale != nullptr; 16x16x32 form only): row p
-    // of the product is scaled by row_scale[p] and added to row row_token[p] of Z -- tokens [own_lo, own_hi) to
-    // z_own (row t - own_lo), the others to z_other (row t) or nowhere (nullptr); leading dimension ldz
-    const float* row_scale;
-    const int* row_token;
-    float* z_own;
-    float* z_other;
-    int own_lo, own_hi;
-    long long ldz;
 };
 
 // One output tile of the grouped GEMM: rows [m0, m_end) of the sorted pair list (inside one expert's segment),
@@ -77,8 +68,6 @@ struct MoeRouteArgs {
     int* seg_off;                 // [E + 1] out
     int* sorted_token;            // [P] out
     int* pair_pos;                // [P] out or nullptr: place of flat pair (token * topk + slot) in the sorted order
-    const float* gate;            // [P] or nullptr: gate value of every flat pair ...
-    float* row_scale;             // ... copied to row_scale[place in the sorted order] (out, [P]) when both are given
     // tile table
     int bm, tiles_n, rows_per_flag, n_flags;
     MoeTile* tile_tab;
@@ -98,7 +87,6 @@ struct TopkReduceArgs {
     float* Z_other;               // ... all other tokens to row t of Z_other (nullptr: not computed)
 };
 hipError_t launch_topk_reduce(const TopkReduceArgs& a, int n_workgroups, hipStream_t stream);
-hipError_t launch_fill_zero(float* p, long long n_vec4, hipStream_t stream);   // p[0 .. 4 n_vec4) = 0, 16-byte aligned
 hipError_t launch_gemm_grouped(const GemmParams& p, int cfg, int grid, hipStream_t stream);
 
 // A tile configuration = a tile shape (bits 0-1) and the MFMA form of the main loop (bit 2): v_mfma_f32_32x32x16_bf16,

@@ -801,19 +801,9 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
 // (A = the routed rows themselves, nothing to wait for).
 // The tile count (one device word) and the tile table come from the caller of this function: the context's reserved
 // buffers, or the library's static scratch.
-// fz (MoE + ReduceScatter): the top-k reduction runs in the GEMM's epilogue; Y is then not written.
-struct FusedTopk {
-    const float* gate;     // [Ttok, topk]
-    float* row_scale;      // [Ttok * topk] scratch: the gate value of every row of the sorted order
-    float* z_own;
-    float* z_other;
-    int own_lo, own_hi;
-    long long ldz;
-};
 static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* A,
                         bool gathered, const void* weights, int32_t* sorted_token, int32_t* seg_off, int32_t* pair_pos,
-                        void* Y, int ldy, int y_dtype, hipStream_t stream, int* n_tiles_word, MoeTile* tab, long long tab_cap,
-                        const FusedTopk* fz = nullptr)
+                        void* Y, int ldy, int y_dtype, hipStream_t stream, int* n_tiles_word, MoeTile* tab, long long tab_cap)
 {
     const long long P = (long long)Ttok * topk;
     const unsigned long long a_bytes = (unsigned long long)(gathered ? Ttok : P) * K * 2;
@@ -856,8 +846,6 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     r.seg_off = seg_off;
     r.sorted_token = sorted_token;
     r.pair_pos = pair_pos;
-    r.gate = fz ? fz->gate : nullptr;
-    r.row_scale = fz ? fz->row_scale : nullptr;
     r.bm = t.bm;
     r.tiles_n = tiles_n;
     r.rows_per_flag = gathered ? tpr / cps : 1;
@@ -892,16 +880,6 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     p.n_tiles_dev = r.n_tiles_dev;
     p.b_group_stride = (long long)N * K;
     p.a_bytes = (unsigned)a_bytes;
-    if (fz) {
-        if (!(cfg & TILE_K32)) return AGG_ERR_INVALID_ARG;     // (moe_rs takes the other route for those configurations)
-        p.row_scale = fz->row_scale;
-        p.row_token = sorted_token;
-        p.z_own = fz->z_own;
-        p.z_other = fz->z_other;
-        p.own_lo = fz->own_lo;
-        p.own_hi = fz->own_hi;
-        p.ldz = fz->ldz;
-    }
     const int grid = (int)(cap < c->num_cus ? cap : c->num_cus);
     return hip_fail(launch_gemm_grouped(p, cfg, grid, stream));
 }
@@ -967,47 +945,23 @@ int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, 
     if (reinterpret_cast<uintptr_t>(R) % (4 * (r_dtype == AGG_F32 ? 4 : 2)) != 0) return AGG_ERR_MISALIGNED;
     if (!aligned16(Y) || !aligned16(gate) || (Z_other && !aligned16(Z_other))) return AGG_ERR_MISALIGNED;
 
-    int rc;
-    float* z_own = const_cast<float*>(slots[c->rank]);
-    // With at most two pairs per token the top-k reduction is done by the GEMM's epilogue: gate x row is added
-    // (fp32 atomic) onto a zeroed Z, and the sum of two products does not depend on which is added first, so the
-    // result is the same bits in every run.  Y then holds only the per-row gate values (its first Ttok * topk words)
-    // and the product never makes the round trip through memory.  More than two pairs per token (or a forced
-    // 32x32x16 configuration, whose epilogue has no such path): grouped GEMM into Y, then the ordered reduction.
-    const bool fused = topk <= 2 && (c->tile_config < 0 || (c->tile_config & TILE_K32));
-    if (fused) {
-        // 1. zero Z: the own slot, and Z_other where it is wanted
-        if ((rc = hip_fail(launch_fill_zero(z_own, (long long)Tr * N / 4, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
-        if (Z_other) {      // (the rows of this rank's own tokens in Z_other are never touched)
-            const long long lo = (long long)c->rank * Tr, hi = lo + Tr;
-            if ((rc = hip_fail(launch_fill_zero(Z_other, lo * N / 4, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
-            if ((rc = hip_fail(launch_fill_zero(Z_other + hi * N, ((long long)Ttok - hi) * N / 4, (hipStream_t)gemm_stream))) != AGG_OK)
-                return rc;
-        }
-        // 2. routing (which also spreads the gate values over the sorted rows) + grouped GEMM + top-k reduction
-        FusedTopk fz{gate, Y, z_own, Z_other, c->rank * Tr, c->rank * Tr + Tr, N};
-        rc = grouped_gemm(c, Ttok, topk, E, N, Kl, topk_ids, H, false, weights2, sorted_token, sorted_expert_offsets,
-                          pair_pos, Y, N, AGG_F32, (hipStream_t)gemm_stream, c->moe_ws, c->moe_tab, c->moe_tab_cap, &fz);
-        if (rc != AGG_OK) return rc;
-    } else {
-        // 1. grouped GEMM on the routed rows (fp32 out)
-        rc = grouped_gemm(c, Ttok, topk, E, N, Kl, topk_ids, H, false, weights2, sorted_token, sorted_expert_offsets,
+    // 1. grouped GEMM on the routed rows (fp32 out)
+    int rc = grouped_gemm(c, Ttok, topk, E, N, Kl, topk_ids, H, false, weights2, sorted_token, sorted_expert_offsets,
                           pair_pos, Y, N, AGG_F32, (hipStream_t)gemm_stream, c->moe_ws, c->moe_tab, c->moe_tab_cap);
-        if (rc != AGG_OK) return rc;
-        // 2. top-k reduction: this rank's tokens into its own slot (first), the others' into Z_other
-        TopkReduceArgs t{};
-        t.Y = Y;
-        t.pair_pos = pair_pos;
-        t.gate = gate;
-        t.T = Ttok;
-        t.topk = topk;
-        t.N = N;
-        t.own_lo = c->rank * Tr;
-        t.own_hi = t.own_lo + Tr;
-        t.Z_own = z_own;
-        t.Z_other = Z_other;
-        if ((rc = hip_fail(launch_topk_reduce(t, c->num_cus * 4, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
-    }
+    if (rc != AGG_OK) return rc;
+    // 2. top-k reduction: this rank's tokens into its own slot (first), the others' into Z_other
+    TopkReduceArgs t{};
+    t.Y = Y;
+    t.pair_pos = pair_pos;
+    t.gate = gate;
+    t.T = Ttok;
+    t.topk = topk;
+    t.N = N;
+    t.own_lo = c->rank * Tr;
+    t.own_hi = t.own_lo + Tr;
+    t.Z_own = const_cast<float*>(slots[c->rank]);
+    t.Z_other = Z_other;
+    if ((rc = hip_fail(launch_topk_reduce(t, c->num_cus * 4, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
     // 3. notify: the own slot is complete; then the reducer, which waits for the peers' signals itself
     int32_t* own_flag = c->signals + (size_t)c->rank * (c->n_signals / W) * kSignalStride;
     for (int ch = 0; ch < c->rs_chunks; ++ch)   // the reduction above completes all row chunks of the slot at once

@@ -745,38 +745,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                     }
                 }
             };
-            // MoE + ReduceScatter (Section 4.1): the top-k reduction is part of this epilogue.  Row p of the grouped
-            // product belongs to token t = row_index2[p]; gate x value is added (fp32 atomic) to row t of Z -- the own
-            // slot for this rank's tokens, Z_other for the others (or nowhere).  Z starts at zero, and with at most two
-            // pairs per token the sum of the two products does not depend on which arrives first.
-            auto epilogue_scatter_add = [&]() {
-                static_for<C_::MB16>([&](auto i_c) {
-                    constexpr int i = decltype(i_c)::value;
-                    const int row = row_w + i * 16 + (lane_e & 15);
-                    float* dst = nullptr;
-                    float scale = 0.f;
-                    if (row < m_lim) {
-                        const int tkn = p.row_token[row];
-                        scale = p.row_scale[row];
-                        if (tkn >= p.own_lo && tkn < p.own_hi) dst = p.z_own + (long long)(tkn - p.own_lo) * p.ldz;
-                        else if (p.z_other) dst = p.z_other + (long long)tkn * p.ldz;
-                    }
-                    const int col0 = n0 + 4 * (lane_e >> 4);
-                    static_for<C_::NB16 * 4>([&](auto jv_c) {
-                        constexpr int j = decltype(jv_c)::value / 4, v = decltype(jv_c)::value % 4;
-                        constexpr int off = j * 16 + v;
-                        const float x = acc_read<(i * C_::NB16 + j) * 4 + v>();
-                        if (dst && col0 + off < p.N) (void)__builtin_amdgcn_global_atomic_fadd_f32(dst + col0 + off, scale * x);
-                    });
-                });
-            };
-            if constexpr (GROUPED && MF == 16) {
-                if (p.row_scale) epilogue_scatter_add();
-                else if (p.c_is_f32) epilogue(float{});
-                else epilogue(__bf16{});
-            } else {
-                if (p.c_is_f32) epilogue(float{}); else epilogue(__bf16{});
-            }
+            if (p.c_is_f32) epilogue(float{}); else epilogue(__bf16{});
         }
 
         // GEMM-RS: count this tile for every chunk of every slice it touches; the last tile of a chunk raises the

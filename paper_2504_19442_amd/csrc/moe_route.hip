@@ -110,7 +110,6 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
         for (int k = 0; k < 4; ++k) {
             if (vv[u][k] == e) {
                 if (a.pair_pos) a.pair_pos[i0 + k] = pos;
-                if (a.row_scale) a.row_scale[pos] = a.gate[i0 + k];
                 a.sorted_token[pos++] = (i0 + k) / a.topk;
             } else if (e == 0 && a.pair_pos && i0 + k < a.P && (unsigned)vv[u][k] >= (unsigned)a.E) {
                 a.pair_pos[i0 + k] = -1;          // an id outside [0, E): the pair is nowhere in the sorted order
@@ -168,23 +167,6 @@ __global__ __launch_bounds__(256) void topk_reduce_kernel(const TopkReduceArgs a
         f32x4* dst = own ? (f32x4*)(a.Z_own + (long long)(t - a.own_lo) * a.N) + j : (f32x4*)(a.Z_other + (long long)t * a.N) + j;
         *dst = z;
     }
-}
-
-// Zero fill as a kernel (a memset node recorded into a HIP graph is not reliable on replay)
-__global__ __launch_bounds__(256) void fill_zero_kernel(float* p, long long n_vec4)
-{
-    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-    const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n_vec4; i += (long long)gridDim.x * 256)
-        ((f32x4*)p)[i] = z;
-}
-
-hipError_t launch_fill_zero(float* p, long long n_vec4, hipStream_t stream)
-{
-    if (n_vec4 <= 0) return hipSuccess;
-    const long long want = (n_vec4 + 255) / 256;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)(want < 2048 ? want : 2048)), dim3(256), 0, stream, p, n_vec4);
-    return hipGetLastError();
 }
 
 hipError_t launch_topk_reduce(const TopkReduceArgs& a, int n_workgroups, hipStream_t stream)
