@@ -57,9 +57,10 @@ struct GemmParams {
 };
 
 // One output tile of the grouped GEMM: rows [m0, m_end) of the sorted pair list (inside one expert's segment),
-// columns of n-tile n_tile, waiting for signals f_lo..f_hi.
+// columns of n-tile n_tile, waiting for signals f_lo..f_hi; of its rows, [st_lo, st_hi) are stored (all of them,
+// unless the caller wants the rows of one token range only; an empty range = the tile is skipped).
 struct MoeTile {
-    int expert, m0, m_end, n_tile, f_lo, f_hi, pad0, pad1;
+    int expert, m0, m_end, n_tile, f_lo, f_hi, st_lo, st_hi;
 };
 
 struct MoeRouteArgs {
@@ -68,6 +69,7 @@ struct MoeRouteArgs {
     int* seg_off;                 // [E + 1] out
     int* sorted_token;            // [P] out
     int* pair_pos;                // [P] out or nullptr: place of flat pair (token * topk + slot) in the sorted order
+    int keep_lo, keep_hi;         // keep_lo < keep_hi: only rows of tokens in [keep_lo, keep_hi) are stored by the GEMM
     // tile table
     int bm, tiles_n, rows_per_flag, n_flags;
     MoeTile* tile_tab;

@@ -801,9 +801,11 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
 // (A = the routed rows themselves, nothing to wait for).
 // The tile count (one device word) and the tile table come from the caller of this function: the context's reserved
 // buffers, or the library's static scratch.
+// keep_lo < keep_hi: only the rows of tokens in [keep_lo, keep_hi) are wanted; tiles without such rows are skipped.
 static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* A,
                         bool gathered, const void* weights, int32_t* sorted_token, int32_t* seg_off, int32_t* pair_pos,
-                        void* Y, int ldy, int y_dtype, hipStream_t stream, int* n_tiles_word, MoeTile* tab, long long tab_cap)
+                        void* Y, int ldy, int y_dtype, hipStream_t stream, int* n_tiles_word, MoeTile* tab, long long tab_cap,
+                        int keep_lo = 0, int keep_hi = 0)
 {
     const long long P = (long long)Ttok * topk;
     const unsigned long long a_bytes = (unsigned long long)(gathered ? Ttok : P) * K * 2;
@@ -846,6 +848,8 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     r.seg_off = seg_off;
     r.sorted_token = sorted_token;
     r.pair_pos = pair_pos;
+    r.keep_lo = keep_lo;
+    r.keep_hi = keep_hi;
     r.bm = t.bm;
     r.tiles_n = tiles_n;
     r.rows_per_flag = gathered ? tpr / cps : 1;
@@ -946,8 +950,12 @@ int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, 
     if (!aligned16(Y) || !aligned16(gate) || (Z_other && !aligned16(Z_other))) return AGG_ERR_MISALIGNED;
 
     // 1. grouped GEMM on the routed rows (fp32 out)
+    // Without Z_other only this rank's tokens are wanted: the GEMM then stores their rows of Y only and skips the tiles
+    // that hold none of them (inside an expert's segment the tokens rise, so the rows of one rank are one run)
+    const int keep_lo = Z_other ? 0 : c->rank * Tr, keep_hi = Z_other ? 0 : keep_lo + Tr;
     int rc = grouped_gemm(c, Ttok, topk, E, N, Kl, topk_ids, H, false, weights2, sorted_token, sorted_expert_offsets,
-                          pair_pos, Y, N, AGG_F32, (hipStream_t)gemm_stream, c->moe_ws, c->moe_tab, c->moe_tab_cap);
+                          pair_pos, Y, N, AGG_F32, (hipStream_t)gemm_stream, c->moe_ws, c->moe_tab, c->moe_tab_cap,
+                          keep_lo, keep_hi);
     if (rc != AGG_OK) return rc;
     // 2. top-k reduction: this rank's tokens into its own slot (first), the others' into Z_other
     TopkReduceArgs t{};

@@ -254,12 +254,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
         if ((G & 7) == 0) t = base + (g & 7) * xcd_slots + (g >> 3); else t = base + g;
         if (t >= total_tiles) continue;
         int m0, n0, m_lim, f_lo = 0, f_hi = -1, expert = 0;
+        int st_lo = 0, st_hi;                 // rows of the output that are stored: [st_lo, st_hi)
         bool from_local = false;
         if constexpr (GROUPED) {
             const MoeTile mt = p.tile_tab[t];
             expert = __builtin_amdgcn_readfirstlane(mt.expert);
             m0 = __builtin_amdgcn_readfirstlane(mt.m0);
             m_lim = __builtin_amdgcn_readfirstlane(mt.m_end);
+            st_lo = __builtin_amdgcn_readfirstlane(mt.st_lo);
+            st_hi = __builtin_amdgcn_readfirstlane(mt.st_hi);
+            if (st_hi <= st_lo) continue;     // no row of this tile is wanted (MoE + ReduceScatter without Z_other)
             n0 = __builtin_amdgcn_readfirstlane(mt.n_tile) * BN;
             f_lo = __builtin_amdgcn_readfirstlane(mt.f_lo);
             f_hi = __builtin_amdgcn_readfirstlane(mt.f_hi);
@@ -293,6 +297,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
             m0 = m_tile * BM;
             n0 = n_tile * BN;
             m_lim = p.M;
+            st_hi = p.M;
             // a tile that lies inside this rank's own shard reads it where the caller keeps it: nothing to wait for
             from_local = p.A_local && m0 >= p.local_lo && m0 + BM <= p.local_hi;
             if (p.flags && !from_local) {
@@ -591,7 +596,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
             const int n_valid = min(BN, p.N - n0);      // columns of this tile inside the matrix
             // where a row of the output goes: C, or (GEMM-RS) the destination of its slice; nullptr = not stored
             auto row_ptr = [&](int row, int esz) -> char* {
-                if (row >= m_lim) return nullptr;
+                if (row < st_lo || row >= st_hi) return nullptr;
                 if (!GROUPED && p.n_slices) {
                     const int w = row / p.slice_rows;
                     if (p.slice_dst[w])
@@ -643,7 +648,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                         const int row0 = row_w + i * 32;
                         // the 32 rows go to C, or (GEMM-RS) to the destination of their slice; a block that
                         // straddles a slice boundary takes the per-row route
-                        const int rows_ok = min(32, m_lim - row0);
+                        const int rows_ok = min(32, st_hi - row0);
+                        const int rows_lo = max(0, st_lo - row0);          // rows of the block before the first stored one
                         bool one_dst = true;          // all rows of the block have one destination matrix
                         char* base = p.C ? (char*)p.C + ((long long)row0 * p.ldc + n0) * esz : nullptr;
                         unsigned ld_bytes = (unsigned)(p.ldc * esz);
@@ -660,7 +666,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                         if constexpr ((32 * cpr) % 64 == 0) {
                             // the common case -- all 32 rows inside the matrix (or segment) and bound for one
                             // destination -- has no per-lane conditions at all: every lane moves `iters` chunks
-                            if (base && rows_ok >= 32 && n_valid == BN && one_dst) {
+                            if (base && rows_ok >= 32 && rows_lo == 0 && n_valid == BN && one_dst) {
                                 static_for<(iters + GRP - 1) / GRP>([&](auto g_c) {
                                     constexpr int it0 = decltype(g_c)::value * GRP;
                                     constexpr int n = (iters - it0 < GRP) ? iters - it0 : GRP;
@@ -702,7 +708,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                             static_for<n>([&](auto k_c) {
                                 constexpr int k = decltype(k_c)::value;
                                 if (one_dst) {
-                                    if (base && rs[k] < rows_ok && ccs[k] < cpr_valid) {
+                                    if (base && rs[k] < rows_ok && rs[k] >= rows_lo && ccs[k] < cpr_valid) {
                                         // C is not read again by this kernel: streaming stores keep it from
                                         // displacing the A and B lines that are
                                         __builtin_nontemporal_store(val[k], (u32x4*)(base + (unsigned)rs[k] * ld_bytes + (unsigned)ccs[k] * 16u));

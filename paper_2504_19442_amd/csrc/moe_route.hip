@@ -134,7 +134,21 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
         const int tok_lo = a.sorted_token[t.m0], tok_hi = a.sorted_token[t.m_end - 1];
         t.f_lo = min(tok_lo / a.rows_per_flag, a.n_flags - 1);
         t.f_hi = min(tok_hi / a.rows_per_flag, a.n_flags - 1);
-        t.pad0 = t.pad1 = 0;
+        t.st_lo = t.m0;
+        t.st_hi = t.m_end;
+        if (a.keep_lo < a.keep_hi) {
+            // tokens rise inside the segment: the rows of tokens in [keep_lo, keep_hi) are one run of the tile's rows
+            auto first_not_below = [&](int tok) {
+                int lo = t.m0, hi = t.m_end;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (a.sorted_token[mid] < tok) lo = mid + 1; else hi = mid;
+                }
+                return lo;
+            };
+            t.st_lo = first_not_below(a.keep_lo);
+            t.st_hi = first_not_below(a.keep_hi);
+        }
         a.tile_tab[first + k] = t;
     }
 }

@@ -121,6 +121,21 @@ def test_moe_rs_tiny(rank, tile):
         run.close()
 
 
+def test_moe_rs_three_experts_per_token():
+    # three pairs per token: the reduction adds the three products in slot order (the same bits in every run)
+    sh = wl.MoeRsShape("moe_rs_top3", 19, 2, 48, 128, 72, 6, 3)
+    inp = wl.make_moe_rs(sh, rank=1)
+    want = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, inp.peer_slots, sh.W, 1)
+    run = MoeRsRun(inp, 1)
+    try:
+        R1, _ = run.run(False)
+        _close(R1.cpu().numpy().astype(np.float64), want, sh.Kl)
+        R2, _ = run.run(True)
+        assert torch.equal(R1, R2)
+    finally:
+        run.close()
+
+
 @pytest.mark.parametrize("chunks", [1, 4])
 def test_moe_rs_integer_inputs_exact(chunks):
     sh = wl.MoeRsShape("moe_rs_int", 18, 2, 40, 128, 40, 7, 2)
