@@ -376,7 +376,7 @@ int agg_set_tile_config(agg_ctx* ctx, int tile_config);
 
 /*
  * Measured ceiling for the MFMA roofline: enqueues on `stream` a kernel in which every wave of one workgroup per
- * compute unit issues `iterations` x 14 v_mfma_f32_32x32x16_bf16 from registers (the GEMM's accumulator pattern, no
+ * compute unit issues `iterations` x 56 v_mfma_f32_16x16x32_bf16 from registers (the GEMM's accumulator pattern, no
  * memory traffic); *flop receives the floating-point operations of the launch (host value, written at once).  The
  * caller times it.  constant_operands = 0: pseudo-random operands in the ranges of the benchmark's inputs (what real
  * data costs in power, hence in clock); 1: every operand element the same (the chip's best case).

@@ -997,8 +997,8 @@ int moe_rs(agg_ctx* c, int Ttok, int topk, int E, int N, int Kl, const void* H, 
 int agg_mfma_ceiling(agg_ctx* c, int iterations, int constant_operands, double* flop, void* stream)
 {
     if (!c || iterations < 1 || iterations > (1 << 24) || !flop) return AGG_ERR_INVALID_ARG;
-    // one workgroup of four waves per compute unit, 14 MFMAs of 32x32x16 per wave and iteration
-    *flop = (double)c->num_cus * 4.0 * (double)iterations * 14.0 * (2.0 * 32 * 32 * 16);
+    // one workgroup of four waves per compute unit, 56 MFMAs of 16x16x32 per wave and iteration
+    *flop = (double)c->num_cus * 4.0 * (double)iterations * 56.0 * (2.0 * 16 * 16 * 32);
     return hip_fail(launch_mfma_ceiling((float*)(c->err + 48), c->num_cus, iterations, constant_operands != 0,
                                         (hipStream_t)stream));
 }

@@ -1,15 +1,16 @@
 // Measured ceiling for the roofline: what the matrix pipes of this chip sustain on the GEMM's own instruction and
-// register pattern when nothing else happens -- no global loads, no LDS traffic, no barriers.  Every wave keeps 14
-// blocks of 32x32 fp32 accumulators (224 registers, as one wave of the 256x224 tile does) and feeds them with
-// v_mfma_f32_32x32x16_bf16 from nine operand fragments held in registers, filled with pseudo-random bf16 values in
-// the ranges of the benchmark's inputs (A uniform in [-1, 1), B scaled by 0.02): the power the pipes draw, and with it
-// the clock the chip holds, depends on how much the operand bits toggle.
+// register pattern when nothing else happens -- no global loads, no LDS traffic, no barriers.  Every wave keeps 56
+// blocks of 16x16 fp32 accumulators (224 registers, as one wave of the 256x224 tile does) and feeds them with
+// v_mfma_f32_16x16x32_bf16 from 4 + 14 operand fragments held in registers, in the main loop's order (the B fragment
+// of a column block against the four A fragments), filled with pseudo-random bf16 values in the ranges of the
+// benchmark's inputs (A uniform in [-1, 1), B scaled by 0.02): the power the pipes draw, and with it the clock the
+// chip holds, depends on how much the operand bits toggle.
 #include "agg_internal.h"
 
 namespace agg {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8c;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16c;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4c;
 
 __device__ inline unsigned mix(unsigned x)
 {
@@ -23,24 +24,24 @@ __device__ inline unsigned mix(unsigned x)
 
 __global__ __launch_bounds__(256) void mfma_ceiling_kernel(float* sink, int iters, int constant_operands)
 {
-    bf16x8c fr[9];
-    for (int s = 0; s < 9; ++s)
+    bf16x8c fa[4], fb[14];
+    for (int s = 0; s < 18; ++s)
         for (int i = 0; i < 8; ++i) {
             const unsigned h = mix(threadIdx.x * 131u + blockIdx.x * 7919u + s * 17u + i);
             const float u = constant_operands ? 1.0f : (h & 0xffff) / 32768.0f - 1.0f;
-            fr[s][i] = (__bf16)(u * (s >= 2 ? 0.02f : 1.0f));
+            if (s < 4) fa[s][i] = (__bf16)u; else fb[s - 4][i] = (__bf16)(u * 0.02f);
         }
-    f32x16c acc[14];
-    for (int j = 0; j < 14; ++j)
-        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    f32x4c acc[56];
+    for (int j = 0; j < 56; ++j)
+        for (int i = 0; i < 4; ++i) acc[j][i] = 0.f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int q = 0; q < 14; ++q)
-            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[q % 2], fr[2 + q / 2], acc[q], 0, 0, 0);
+        for (int q = 0; q < 56; ++q)
+            acc[(q % 4) * 14 + q / 4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[q / 4], fa[q % 4], acc[(q % 4) * 14 + q / 4], 0, 0, 0);
     }
     float s = 0.f;
-    for (int j = 0; j < 14; ++j)
-        for (int i = 0; i < 16; ++i) s += acc[j][i];
+    for (int j = 0; j < 56; ++j)
+        for (int i = 0; i < 4; ++i) s += acc[j][i];
     if (s == 123.456f) sink[threadIdx.x] = s;      // keeps the loop alive; practically never taken
 }
 
