@@ -88,6 +88,9 @@ def main() -> int:
     ap.add_argument("--tile", type=int, default=-1)
     ap.add_argument("--chunks", type=int, default=4, help="signals per shard")
     ap.add_argument("--producer-wgs", type=int, default=0)
+    ap.add_argument("--wide-producer", action="store_true",
+                    help="copy kernel with four waves per workgroup (default: one wave per workgroup: the same fused "
+                         "time, for a quarter of the registers and issue slots the copy takes on every compute unit)")
     ap.add_argument("--t-local", action="store_true",
                     help="read the own shard from T like any other (default: in place, where the caller keeps it, "
                          "with the local copy into T done last)")
@@ -218,10 +221,15 @@ def main() -> int:
             self.run = AgGemmRun(self.inp, rank, chunks_per_shard=args.chunks)
             self.ctx = self.run.ctx
             self.ctx.set_tile_config(args.tile)
-            self.local_flag = 0
+            # The copy kernel's workgroups: one wave each where the GEMM runs for several rounds of tiles (the copy then
+            # takes a quarter of the registers and issue slots on the compute units it shares, and arrives in time all
+            # the same), four waves where the GEMM is a single round and waits for the last shard to land
+            rounds = ((shape.M + 255) // 256) * ((shape.N + 223) // 224) / 256.0
+            self.narrow = (not args.wide_producer) and rounds >= 2.0
+            self.local_flag = agg.PRODUCER_NARROW if self.narrow else 0
             if not args.t_local:
                 self.ctx.set_local_shard(self.run.remote[rank])
-                self.local_flag = agg.PRODUCER_LOCAL_LAST
+                self.local_flag |= agg.PRODUCER_LOCAL_LAST
             self.C = torch.empty((shape.M, shape.N), device="cuda", dtype=torch.bfloat16)
             self.prod, self.cons = self.run.prod, self.run.cons
             self.prod_h, self.cons_h = self.prod.cuda_stream, self.cons.cuda_stream
@@ -239,8 +247,11 @@ def main() -> int:
                         stream or self.cons)
 
         def produce(self, stream, mode=None):
-            agg.ag_producer_emulate(self.ctx, self.run.remote, None, (agg.PRODUCER_KERNEL if mode is None else mode)
-                                    | self.local_flag, args.producer_wgs, stream)
+            flags = self.local_flag
+            if mode is not None and mode != agg.PRODUCER_KERNEL:
+                flags &= ~agg.PRODUCER_NARROW                 # (the narrow form exists for the copy kernel only)
+            agg.ag_producer_emulate(self.ctx, self.run.remote, None, (agg.PRODUCER_KERNEL if mode is None else mode) | flags,
+                                    args.producer_wgs, stream)
 
         def mark(self):
             hev.record(self.ev_cons_done, self.cons_h)
@@ -350,7 +361,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": shape.name, "W": shape.W, "rank": rank, "M": M, "N": N, "K": K,
                    "signals_per_shard": args.chunks, "tile_config": args.tile, "out": "bf16",
-                   "producer": "copy kernel on the producer stream",
+                   "producer": "copy kernel on the producer stream, " + ("one wave" if prob.narrow else "four waves")
+                               + " per workgroup, one workgroup per compute unit",
                    "own_shard": "from T" if args.t_local else "read in place, copied into T last"},
         "fraction_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": {"bound": "mfma", "achieved": round(flops / (kern_ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS,
@@ -369,6 +381,13 @@ def main() -> int:
         n2, rounds = max(5, args.steps // 5), 5
         out["overlap"], t_gemm, t_copy = prob.overlap(max(n2, 20), rounds)
         out["targets"]["met"] = bool(out["fraction_of_bf16_peak"] >= 0.70 and out["overlap"]["hidden_fraction"] >= 0.90)
+        # the same with the other width of the copy kernel's workgroups, for comparison
+        saved = prob.local_flag
+        prob.local_flag ^= agg.PRODUCER_NARROW
+        ov2, _, _ = prob.overlap(max(n2, 20), 3)
+        prob.local_flag = saved
+        out["overlap_other_producer_width"] = dict(ov2, producer=("four waves" if prob.narrow else "one wave")
+                                                   + " per workgroup")
 
         # the 8B-MLP-shaped workload (256 tiles of 256x224: one round over the CUs), same protocol
         if not args.shape and shape.name != wl.AG_8B.name:

@@ -55,7 +55,10 @@ enum { AGG_PRODUCER_KERNEL = 0,              /* copy kernel on a few CUs, releas
        AGG_PRODUCER_SDMA = 1,               /* copy engine (no compute units) + one 4-byte copy per signal */
        AGG_PRODUCER_LINKS = 2,              /* full mesh: every peer's shard on a "link" of its own, all at once, chunk by chunk */
        AGG_PRODUCER_SKIP_LOCAL = 0x100,     /* OR into mode: do not (re)copy the local shard in this call */
-       AGG_PRODUCER_LOCAL_LAST = 0x200 };    /* OR into mode: copy the local shard after the peers' instead of first */
+       AGG_PRODUCER_LOCAL_LAST = 0x200,     /* OR into mode: copy the local shard after the peers' instead of first */
+       AGG_PRODUCER_NARROW = 0x400 };       /* OR into mode (copy kernel): workgroups of one wave instead of four, so that
+                                               the copy takes a quarter of the register file and issue slots of the compute
+                                               units it shares with the consumer (Section 3.8: few resources for communication) */
 
 /* One signal word per AGG_SIGNAL_STRIDE int32 (each signal owns a 128-byte line). */
 #define AGG_SIGNAL_STRIDE 32

@@ -13,7 +13,7 @@ import os
 __all__ = [
     "AggError", "Ctx", "symm_alloc", "signal_reset", "signal_set", "ag_producer_emulate", "ag_gemm",
     "rs_reduce", "gemm_rs", "gemm_rs_scatter", "ag_moe_gemm", "ag_moe_gemm_static", "agg_reserve_b_kn", "agg_reserve_moe", "moe_rs", "agg_autotune_ag_gemm", "agg_mfma_ceiling", "agg_status", "agg_strerror", "agg_device_info", "lib_path",
-    "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL", "PRODUCER_LOCAL_LAST",
+    "BF16", "F32", "B_NK", "B_KN", "PRODUCER_KERNEL", "PRODUCER_SDMA", "PRODUCER_LINKS", "PRODUCER_SKIP_LOCAL", "PRODUCER_LOCAL_LAST", "PRODUCER_NARROW",
     "ORDER_ROTATED", "ORDER_SUBCHUNK", "SIGNAL_STRIDE",
     "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED_SHAPE", "ERR_MISALIGNED", "ERR_HIP", "ERR_TIMEOUT", "ERR_NOMEM", "ERR_NOT_FOUND", "ERR_IO", "ERR_NOT_RESERVED",
     "agg_tune_table_size", "agg_tune_table_clear", "agg_tune_table_put", "agg_tune_table_get", "agg_tune_table_save", "agg_tune_table_load",
@@ -23,7 +23,7 @@ __all__ = [
 
 BF16, F32 = 0, 1
 B_NK, B_KN = 0, 1
-PRODUCER_KERNEL, PRODUCER_SDMA, PRODUCER_LINKS, PRODUCER_SKIP_LOCAL, PRODUCER_LOCAL_LAST = 0, 1, 2, 0x100, 0x200
+PRODUCER_KERNEL, PRODUCER_SDMA, PRODUCER_LINKS, PRODUCER_SKIP_LOCAL, PRODUCER_LOCAL_LAST, PRODUCER_NARROW = 0, 1, 2, 0x100, 0x200, 0x400
 ORDER_ROTATED, ORDER_SUBCHUNK = 0, 1
 SIGNAL_STRIDE = 32
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_SHAPE, ERR_MISALIGNED, ERR_HIP, ERR_TIMEOUT, ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6

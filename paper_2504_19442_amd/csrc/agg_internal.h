@@ -124,7 +124,7 @@ struct ProducerArgs {
     int link_wgs;                 // full-mesh mode: workgroups per link (set by launch_producer_links)
     double ticks_per_byte;        // full-mesh mode: wall-clock ticks a link takes per byte (0 = not paced)
 };
-hipError_t launch_producer(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
+hipError_t launch_producer(const ProducerArgs& a, int n_workgroups, int threads, hipStream_t stream);
 hipError_t launch_producer_links(const ProducerArgs& a, int n_workgroups, hipStream_t stream);
 hipError_t launch_signal_set(int* flag, int value, const int* value_ptr, hipStream_t stream);
 hipError_t launch_epoch_advance(int* epoch_word, hipStream_t stream);

@@ -376,7 +376,8 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     if (!c || !remote_shards) return AGG_ERR_INVALID_ARG;
     const bool skip_local = (mode & AGG_PRODUCER_SKIP_LOCAL) != 0;
     const bool local_last = (mode & AGG_PRODUCER_LOCAL_LAST) != 0 && !skip_local;
-    mode &= ~(AGG_PRODUCER_SKIP_LOCAL | AGG_PRODUCER_LOCAL_LAST);
+    const int threads = (mode & AGG_PRODUCER_NARROW) ? 64 : 256;
+    mode &= ~(AGG_PRODUCER_SKIP_LOCAL | AGG_PRODUCER_LOCAL_LAST | AGG_PRODUCER_NARROW);
     if (mode != AGG_PRODUCER_KERNEL && mode != AGG_PRODUCER_SDMA && mode != AGG_PRODUCER_LINKS) return AGG_ERR_INVALID_ARG;
     if (n_workgroups < 0 || n_workgroups > 4096) return AGG_ERR_INVALID_ARG;
     const int W = c->W;
@@ -420,7 +421,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     }
     if (mode == AGG_PRODUCER_KERNEL) {
         const int nwg = n_workgroups > 0 ? n_workgroups : (c->producer_wgs > 0 ? c->producer_wgs : c->num_cus);
-        return hip_fail(launch_producer(a, nwg, st));
+        return hip_fail(launch_producer(a, nwg, threads, st));
     }
     if (mode == AGG_PRODUCER_LINKS) {
         // the local copy first, at full width (it crosses no link); then every peer on a link of its own
@@ -431,7 +432,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
         if (has_local && !local_last) {
             ProducerArgs loc = a;
             loc.n_jobs = 1;
-            int rc = hip_fail(launch_producer(loc, nwg, st));
+            int rc = hip_fail(launch_producer(loc, nwg, threads, st));
             if (rc != AGG_OK) return rc;
         }
         ProducerArgs rem = a;
@@ -448,7 +449,7 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
         loc.n_jobs = 1;
         loc.src[0] = a.src[local_job];
         loc.rank_of[0] = a.rank_of[local_job];
-        return hip_fail(launch_producer(loc, nwg, st));
+        return hip_fail(launch_producer(loc, nwg, threads, st));
     }
     // copy engine: one transfer per chunk, then a second, tiny transfer that carries only the signal (Section 3.6)
     if (!c->device_epoch) HIP_TRY(launch_signal_set(c->epoch_word, c->epoch, nullptr, st));   // else the word is the epoch already

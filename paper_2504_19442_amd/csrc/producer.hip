@@ -23,6 +23,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
 {
     const int tid = threadIdx.x;
+    const unsigned span = blockDim.x * 16u;         // bytes one load instruction of the workgroup covers
     const int epoch = a.epoch_ptr ? __hip_atomic_load(a.epoch_ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.epoch;
     const int team = a.team;
     const int n_teams = gridDim.x / team;
@@ -47,15 +48,15 @@ __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
         const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(d, 0, bytes, 0x00020000);
         // four independent 16-byte loads in flight per lane; out-of-range lanes of the last round load zero
         // and store nothing (the descriptors bound both)
-        for (unsigned off = tid * 16u; off < bytes; off += 4u * 4096u) {
+        for (unsigned off = tid * 16u; off < bytes; off += 4u * span) {
             u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, NT);
-            u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 4096u, 0, NT);
-            u32x4 v2 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 8192u, 0, NT);
-            u32x4 v3 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 12288u, 0, NT);
+            u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + span, 0, NT);
+            u32x4 v2 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 2u * span, 0, NT);
+            u32x4 v3 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 3u * span, 0, NT);
             __builtin_amdgcn_raw_buffer_store_b128(v0, rd, off, 0, WT);
-            __builtin_amdgcn_raw_buffer_store_b128(v1, rd, off + 4096u, 0, WT);
-            __builtin_amdgcn_raw_buffer_store_b128(v2, rd, off + 8192u, 0, WT);
-            __builtin_amdgcn_raw_buffer_store_b128(v3, rd, off + 12288u, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v1, rd, off + span, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v2, rd, off + 2u * span, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v3, rd, off + 3u * span, 0, WT);
         }
         // signal: the last workgroup of the team to finish the chunk sets it (set_signal after the copy, Algorithm 2)
         __builtin_amdgcn_s_waitcnt(0);              // every store of this lane has completed
@@ -81,6 +82,7 @@ __global__ __launch_bounds__(256) void producer_kernel(const ProducerArgs a)
 __global__ __launch_bounds__(256) void producer_links_kernel(const ProducerArgs a)
 {
     const int tid = threadIdx.x;
+    const unsigned span = 4096u;                    // bytes one load instruction of the workgroup covers (256 threads)
     const int epoch = a.epoch_ptr ? __hip_atomic_load(a.epoch_ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.epoch;
     const int link = blockIdx.x % a.n_jobs, j = blockIdx.x / a.n_jobs;
     if (j >= a.link_wgs) return;
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(256) void producer_links_kernel(const ProducerArgs 
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(s), 0, bytes, 0x00020000);
         const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(d, 0, bytes, 0x00020000);
         int step = 0;
-        for (unsigned off = tid * 16u; off - tid * 16u < bytes; off += 4u * 4096u, ++step) {
+        for (unsigned off = tid * 16u; off - tid * 16u < bytes; off += 4u * span, ++step) {
             if (a.ticks_per_byte > 0.0) {
                 // bytes the link has moved when all its workgroups have done `step` steps of this chunk
                 const double before = (double)c * (double)a.chunk_bytes + (double)step * 16384.0 * a.link_wgs;
@@ -105,13 +107,13 @@ __global__ __launch_bounds__(256) void producer_links_kernel(const ProducerArgs 
                 while (wall_clock64() < target) __builtin_amdgcn_s_sleep(4);
             }
             u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, NT);
-            u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 4096u, 0, NT);
-            u32x4 v2 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 8192u, 0, NT);
-            u32x4 v3 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 12288u, 0, NT);
+            u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + span, 0, NT);
+            u32x4 v2 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 2u * span, 0, NT);
+            u32x4 v3 = __builtin_amdgcn_raw_buffer_load_b128(rs, off + 3u * span, 0, NT);
             __builtin_amdgcn_raw_buffer_store_b128(v0, rd, off, 0, WT);
-            __builtin_amdgcn_raw_buffer_store_b128(v1, rd, off + 4096u, 0, WT);
-            __builtin_amdgcn_raw_buffer_store_b128(v2, rd, off + 8192u, 0, WT);
-            __builtin_amdgcn_raw_buffer_store_b128(v3, rd, off + 12288u, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v1, rd, off + span, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v2, rd, off + 2u * span, 0, WT);
+            __builtin_amdgcn_raw_buffer_store_b128(v3, rd, off + 3u * span, 0, WT);
         }
         if (a.ticks_per_byte > 0.0) {      // the chunk is not announced before the link could have delivered it
             const long long target = t0 + (long long)((double)(c + 1) * (double)a.chunk_bytes * a.ticks_per_byte);
@@ -145,7 +147,9 @@ __global__ void epoch_advance_kernel(int* epoch_word)
     __hip_atomic_store(epoch_word, e + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-hipError_t launch_producer(const ProducerArgs& a_in, int n_workgroups, hipStream_t stream)
+// threads: 256 (four waves per workgroup) or 64 (one wave: a narrow producer that leaves the consumer more of every
+// compute unit it shares)
+hipError_t launch_producer(const ProducerArgs& a_in, int n_workgroups, int threads, hipStream_t stream)
 {
     ProducerArgs a = a_in;
     // team size: slices of at least 64 KiB, at most the whole grid on one chunk
@@ -153,7 +157,7 @@ hipError_t launch_producer(const ProducerArgs& a_in, int n_workgroups, hipStream
     if (team < 1) team = 1;
     if (team > n_workgroups) team = n_workgroups;
     a.team = (int)team;
-    hipLaunchKernelGGL(producer_kernel, dim3(n_workgroups), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(producer_kernel, dim3(n_workgroups), dim3(threads), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -149,6 +149,26 @@ def test_new_shard_contents_in_the_next_epoch_are_seen_without_any_poison_betwee
         run.close()
 
 
+def test_narrow_producer_delivers_the_same_bytes():
+    """The copy kernel with workgroups of one wave (AGG_PRODUCER_NARROW): T ends up byte for byte the gathered shards and
+    the product is bit-identical to the run with the four-wave producer, for whole and ragged chunk sizes."""
+    for shape, chunks in ((wl.AG_TINY, 2), (wl.AG_RAGGED, 1), (wl.AG_8B, 4)):
+        inp = wl.make_ag_gemm(shape)
+        run = AgGemmRun(inp, 1, chunks_per_shard=chunks)
+        try:
+            base = run.run(consumer_first=False)
+            for nwg in (0, 3, 37):
+                C = run.run([0] + list(range(2, shape.W)), mode=agg.PRODUCER_KERNEL | agg.PRODUCER_NARROW,
+                            n_workgroups=nwg)
+                assert torch.equal(C.view(torch.int32), base.view(torch.int32)), (shape.name, nwg)
+                n = shape.W * shape.Ms * shape.K
+                from harness import _tensor_from_ptr
+                T = _tensor_from_ptr(run.ctx.staging, n).view(torch.int16).cpu().numpy().view(np.uint16)
+                assert np.array_equal(T.reshape(shape.M, shape.K), np.concatenate(inp.shards))
+        finally:
+            run.close()
+
+
 def test_copy_engine_producer():
     inp = wl.make_ag_gemm(wl.AG_TINY)
     ref = oracle.ag_gemm(inp.shards, inp.B_kn, 1)
