@@ -9,27 +9,33 @@
 // pair of Section 2.2.
 //
 // Main loop: K is cut into stages of 64, so that every row of a tile is fetched as one whole 128-byte line
-// (the L2 hands out lines: asking for half a line at a time halves its useful bandwidth, and the loop was
-// bound by exactly that).  A and B tiles go from global memory straight into LDS (buffer_load_dwordx4 ... lds,
-// 16 bytes per lane) into a ring that takes up nearly all of the LDS (two stages and a third of a third one).  Rows are 128 bytes in LDS; the 16-byte chunk c of row r
-// sits in slot c ^ ((r >> 1) & 7), which makes the ds_read_b128 operand fetches bank-conflict free.  Each
-// wave owns BM/4 rows and all BN columns of the tile and feeds v_mfma_f32_32x32x16_bf16; a stage is four
-// quarter-steps of K=16, and the fragments of a quarter-step are read from LDS while the previous one is on
-// the matrix pipe (two register sets).  One workgroup barrier per stage, placed before the last quarter-step:
-// by then every wave has read all it needs of the current stage, so the loads of the stage after next can
-// start into its buffer at once.  Memory instructions are dealt out one per MFMA (a wave issues in order
-// and a memory instruction is slow to issue, so bunches of them between two MFMAs starve the matrix pipe).
+// (the L2 hands out lines: asking for half a line at a time halves its useful bandwidth).  A and B tiles go
+// from global memory straight into LDS (buffer_load_dwordx4 ... lds, 16 bytes per lane) into a ring that takes
+// up nearly all of the LDS (two stages and a third of a third one).  Rows are 128 bytes in LDS; the 16-byte
+// chunk c of row r sits in slot c ^ ((r >> 1) & 7), which makes the ds_read_b128 operand fetches bank-conflict
+// free.  Each wave owns BM/4 rows and all BN columns of the tile.  Two forms of the loop (template parameter MF):
+//   MF = 16: v_mfma_f32_16x16x32_bf16.  A stage is two half-steps of K = 32; a half-step is BN/16 groups of MFMAs, group j
+//            using the B fragment of column block j against the wave's A fragments; the B fragment registers
+//            are refilled for the next half-step as soon as their group is done.  Half the accumulator traffic per
+//            flop of the other form: the chip, which is power-limited under this load, holds a higher clock.
+//   MF = 32: v_mfma_f32_32x32x16_bf16.  A stage is four quarter-steps of K = 16, fragments double-buffered.
+// One workgroup barrier per stage; memory instructions are dealt out between the MFMAs (a wave issues in
+// order, and bunches of memory instructions between two MFMAs starve the matrix pipe).
 // The MFMA computes the transposed block (B fragment as first operand), so that a lane ends up holding
 // four consecutive columns of one output row; the epilogue stages each wave's rows through LDS and
 // stores them to C as whole 16-byte row chunks.
 //
-// Registers: the fp32 accumulators live in accumulator registers a0..a(MB*NB*16-1) that only the inline
+// Registers: the fp32 accumulators live in accumulator registers a0..a(ACC-1) that only the inline
 // asm of this file touches (MFMA, zeroing, read-out); the compiler allocates the ordinary registers and is
-// capped so that the kernel takes 448 of the 512 registers of a SIMD.  The 64 left over are what lets one
+// capped so that the kernel takes at most 448 of the 512 registers of a SIMD.  The rest is what lets one
 // wave of a small kernel (the producer's copy waves, the reducer) run beside a consumer wave on every
 // SIMD: communication and computation share all CUs instead of splitting them (Section 3.8).
 #pragma once
 #include "agg_internal.h"
+
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "this kernel names gfx950 instructions and registers (MFMA forms, accumulator registers, global->LDS loads)"
+#endif
 
 #include <numeric>
 #include <type_traits>

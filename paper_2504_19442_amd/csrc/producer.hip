@@ -4,7 +4,18 @@
 // registers, so its waves fit beside the consumer's on any CU (Section 3.8, resource partition).
 #include "agg_internal.h"
 
-#define AGG_PROD_LOAD_AUX 2          // cache policy bits of the copy's loads: 2 = nt (streaming)
+// Cache policy bits of the buffer instructions below, in the gfx940 / gfx950 encoding of the `aux` operand:
+// 2 = nt (streaming) on the loads, 16 = sc1 (agent scope: written through this XCD's L2) on the stores.  The
+// publication of a chunk rests on three properties of this hardware, not on the language's memory model:
+//   1. a store with sc1 has reached memory (not just the writer's L2) when s_waitcnt vmcnt(0) returns;
+//   2. the signal is a relaxed agent-scope store to a line of its own, issued after that wait, so it cannot overtake the data;
+//   3. the consumer's acquire (buffer_inv sc1, executed by the wave that saw the signal) drops its XCD's L2 and its
+//      CU's L1 copies of lines written elsewhere, so its loads of the chunk go to memory.
+// Another target would need these re-checked: the build refuses it.
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "the cache policy bits and the publication scheme of this file are those of gfx950"
+#endif
+#define AGG_PROD_LOAD_AUX 2
 
 namespace agg {
 
