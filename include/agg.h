@@ -353,7 +353,9 @@ int agg_set_link_rate(agg_ctx* ctx, double gigabytes_per_second);
  * scatter; tensor parallel over K).
  * H: bf16 [Ttok*topk, Klocal], the routed rows in the order of ag_moe_gemm's output (pairs sorted by (expert, token,
  * slot)); weights2: bf16 [E][N][Klocal]; topk_ids as in ag_moe_gemm; gate: fp32 [Ttok, topk].
- *   Y[p, :] = H[p, :] . W2_expert(p)                       (Y: caller's fp32 workspace [Ttok*topk, N], overwritten)
+ *   Y[p, :] = H[p, :] . W2_expert(p)                       (Y: caller's fp32 workspace [Ttok*topk, N], overwritten; if
+ *                                                           Z_other is NULL only the rows of this rank's tokens are
+ *                                                           computed and stored, the other rows of Y keep what they held)
  *   Z[t, :] = sum_s gate[t, s] * Y[pair_pos[t*topk+s], :]  (fp32, slots in order; this rank's tokens go straight into
  *                                                           slots[rank], the others into row t of Z_other, or nowhere
  *                                                           if Z_other is NULL)
