@@ -287,14 +287,14 @@ int agg_reserve_moe(agg_ctx* ctx, int Ttok, int topk, int E, int N);
 
 /*
  * ag_moe_gemm for callers that cannot allocate device memory and cannot ask a context to (code under HIP graph
- * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the tile count and
- * tile table live in a fixed 1 MiB array in the library's own device image (one copy per GPU, held until the process
- * ends) instead of a reserved workspace.  The call allocates nothing, frees nothing and does not synchronise.  It
- * returns AGG_ERR_UNSUPPORTED_SHAPE when the table of the problem could exceed the array:
- * (Ttok * topk / 128 + E) * ceil(N / 128) entries of 32 bytes must fit in 1 MiB - 256 bytes (32760 entries; the
- * Table 4 shape needs 3072).  All contexts on one GPU share the array, and it keeps the last call's contents (every
- * entry a call reads it has written first, so nothing needs clearing): two calls that overlap in time on one GPU
- * race, whatever their contexts and streams -- order them.
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the routing's
+ * counters and the tile table live in a fixed array of 1056 KiB in the library's own device image (one copy per GPU,
+ * held until the process ends) instead of a reserved workspace.  The call allocates nothing, frees nothing and does
+ * not synchronise.  It returns AGG_ERR_UNSUPPORTED_SHAPE when the table of the problem could exceed the array:
+ * (Ttok * topk / 128 + E) * ceil(N / 128) entries of 32 bytes must fit in 32760 entries (the Table 4 shape needs
+ * 3072).  All contexts on one GPU share the array, and it keeps the last call's contents (the counters return to their
+ * rest state at the end of every call and every table entry a call reads it has written first, so nothing needs
+ * clearing): two calls that overlap in time on one GPU race, whatever their contexts and streams -- order them.
  */
 int ag_moe_gemm_static(agg_ctx* ctx, int Ttok, int topk, int E, int N, int K,
                        const int32_t* topk_ids, const void* weights,

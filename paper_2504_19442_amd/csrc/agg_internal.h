@@ -75,7 +75,15 @@ struct MoeRouteArgs {
     MoeTile* tile_tab;
     int tab_capacity;
     int* n_tiles_dev;
+    unsigned char* ctrl;          // the routing's control block (kMoeCtrlBytes of device memory, all zero before its first use)
+    long long wait_ticks;         // bound of the wait for the other experts' counts, in wall-clock ticks
+    int* err;                     // device word: set to 1 when that wait is given up
 };
+// Control block of the MoE routing: the tile count (int, read by the grouped GEMM), the number of finished routing
+// calls, the ticket counter, and one tagged count per expert.
+constexpr int kMoeMaxExperts = 4096;
+constexpr size_t kMoeCtrlCall = 8, kMoeCtrlTicket = 16, kMoeCtrlCounts = 256;
+constexpr size_t kMoeCtrlBytes = kMoeCtrlCounts + (size_t)kMoeMaxExperts * 8;
 hipError_t launch_moe_route(const MoeRouteArgs& a, hipStream_t stream);
 
 // Top-k reduction of MoE + ReduceScatter: Z[t, :] = sum_s gate[t, s] * Y[pair_pos[t * topk + s], :]
@@ -180,7 +188,7 @@ struct agg_ctx {
     double link_GBps;    // pace of a link of the full-mesh producer (0 = not paced)
     hipStream_t producer_stream, consumer_stream;
     // grouped GEMM workspace (sized by agg_reserve_moe; no other call allocates it)
-    int* moe_ws;          // the tile count of the launch under way (one word)
+    int* moe_ws;          // the MoE routing's control block (kMoeCtrlBytes; its first word is the tile count of the launch under way)
     agg::MoeTile* moe_tab;
     int moe_tab_cap;
     uint16_t* b_nk;       // [N][K] copy of a B that was given as [K][N] (sized by agg_reserve_b_kn)

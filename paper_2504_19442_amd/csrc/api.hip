@@ -104,10 +104,11 @@ int resolve_b(agg_ctx* c, const void* B, int ldb, int b_layout, int N, int K, hi
 }
 
 // ---- device memory that no call allocates: a fixed array in the library's image, one copy per GPU, used by
-// ag_moe_gemm_static for the grouped GEMM's tile count and tile table.  Host code never uses the array's name as an
+// ag_moe_gemm_static for the MoE routing's control block and the grouped GEMM's tile table.  Host code never uses the array's name as an
 // address: the device address is looked up once per context (symm_alloc, with the context's device current).
-constexpr size_t kStaticScratchBytes = 1u << 20;
-constexpr size_t kStaticTabOffset = 256;                   // the tile count sits in the first line, the table after it
+constexpr size_t kStaticTabOffset = kMoeCtrlBytes;         // the routing's control block first, the table after it
+constexpr size_t kStaticTabEntries = 32760;
+constexpr size_t kStaticScratchBytes = kStaticTabOffset + kStaticTabEntries * sizeof(MoeTile);   // 1056 KiB
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // Upper bound of the grouped GEMM's tile table over all tile configurations: sum over experts of
@@ -357,7 +358,8 @@ int agg_reserve_moe(agg_ctx* c, int Ttok, int topk, int E, int N)
     if (cap > (1ll << 28)) return AGG_ERR_UNSUPPORTED_SHAPE;
     if (!c->moe_ws) {
         HIP_TRY(hipDeviceSynchronize());
-        HIP_TRY(hipMalloc((void**)&c->moe_ws, 256));
+        HIP_TRY(hipMalloc((void**)&c->moe_ws, kMoeCtrlBytes));
+        HIP_TRY(hipMemset(c->moe_ws, 0, kMoeCtrlBytes));         // the routing's counters start at zero
     }
     if (c->moe_tab_cap < cap) {
         HIP_TRY(hipDeviceSynchronize());
@@ -800,8 +802,8 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
 
 // Routing + grouped GEMM, shared by ag_moe_gemm (A = T, rows gathered by token, tiles gated by the signals) and moe_rs
 // (A = the routed rows themselves, nothing to wait for).
-// The tile count (one device word) and the tile table come from the caller of this function: the context's reserved
-// buffers, or the library's static scratch.
+// The routing's control block (its first word is the tile count) and the tile table come from the caller of this
+// function: the context's reserved buffers, or the library's static scratch.
 // keep_lo < keep_hi: only the rows of tokens in [keep_lo, keep_hi) are wanted; tiles without such rows are skipped.
 static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* A,
                         bool gathered, const void* weights, int32_t* sorted_token, int32_t* seg_off, int32_t* pair_pos,
@@ -857,6 +859,9 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     r.n_flags = c->n_signals;
     r.tile_tab = tab;
     r.tab_capacity = (int)cap;
+    r.ctrl = (unsigned char*)n_tiles_word;
+    r.wait_ticks = wait_ticks(c);
+    r.err = c->err;
     int rc = hip_fail(launch_moe_route(r, stream));
     if (rc != AGG_OK) return rc;
 

@@ -6,124 +6,194 @@
 
 namespace agg {
 
-constexpr int kMaxExperts = 4096;     // histogram bins held in LDS
+constexpr int kSegTokLds = 2048;      // an expert's sorted tokens are kept in LDS for the tile entries up to this many
+constexpr int kRouteWaves = 16, kRouteThreads = 64 * kRouteWaves;
+constexpr int kRouteSteps = 4;
+constexpr int kChunk = kRouteWaves * kRouteSteps * 256;     // pairs taken at a time: 16 waves x 4 steps x 64 lanes x 4 pairs
 
-// One kernel, one workgroup per expert.  Every workgroup builds the full histogram of the ids in LDS (counts do not
-// depend on the order of the atomic adds), takes its own segment offset and first tile index from the prefix sums,
-// then writes the tokens of its expert's pairs in (token, slot) order -- the order of the flat pair index -- and
-// the expert's tile entries.  Tiles of an expert are listed n-tile by n-tile, the m-tiles of one n-tile next to
-// each other, so that the workgroups of one XCD (which take consecutive tiles) read the same rows of that
-// expert's weights at the same time.  Workgroup 0 also writes the segment offsets and the tile count.
-__global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
+// One kernel, one workgroup per expert.  Only one pair in E belongs to the expert, so the work per pair is kept to a
+// compare: a wave takes 1024 consecutive pairs of a chunk (a lane 4 consecutive ones in each of 4 steps), the place
+// of a matching pair among the workgroup's matches comes from ballots and lane-mask bit counts, the matches are
+// compacted into LDS as offsets inside the chunk, and only then turned into tokens and stored, one match per lane:
+// the tokens of the expert's pairs in (token, slot) order -- the order of the flat pair index.
+//
+// The segment offset of an expert is the sum of the counts of the experts before it.  Every workgroup publishes its
+// count in the control block and reads those of the experts before it (waiting for them where needed; it compacts
+// its matches meanwhile).  A workgroup takes its expert from a ticket counter, not from its index in the grid: a
+// workgroup that holds ticket e knows that the holders of the tickets below e are already running, so its wait ends
+// whatever order the hardware starts workgroups in.  Counts are tagged with the number of the call (a device word
+// that the holder of the last ticket advances, after which it puts the ticket counter back to zero): entries of earlier
+// calls are never taken for this call's, nothing has to be cleared between calls, and a launch replayed from a HIP
+// graph works like a fresh one.  Waits are bounded by the context's time limit like the GEMM's waits for signals.
+//
+// Tiles of an expert are listed n-tile by n-tile, the m-tiles of one n-tile next to each other, so that the
+// workgroups of one XCD (which take consecutive tiles) read the same rows of that expert's weights at the same time.
+__global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRouteArgs a)
 {
-    const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    extern __shared__ int hist[];                 // [E] counts
-    __shared__ int wave_cnt[2][8][4];
-    __shared__ int s_seg_lo, s_first;
-    for (int i = tid; i < a.E; i += 256) hist[i] = 0;
-    __syncthreads();
-    // ---- pass 1: histogram (four ids per lane per step)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ int s_e, s_cnt[kRouteWaves], wave_tot[2][kRouteWaves], s_seg_lo, s_first;
+    __shared__ unsigned s_tag;
+    __shared__ int seg_tok[kSegTokLds];           // this expert's tokens in sorted order, while they fit
+    __shared__ unsigned short cidx[kChunk];       // the chunk's matching pairs (offset inside the chunk), in order
+    unsigned* const call_word = (unsigned*)(a.ctrl + kMoeCtrlCall);
+    unsigned* const ticket_word = (unsigned*)(a.ctrl + kMoeCtrlTicket);
+    unsigned long long* const counts = (unsigned long long*)(a.ctrl + kMoeCtrlCounts);
+    // All loads of a chunk are issued before the first use: one memory latency per chunk.  When all pairs fit one
+    // chunk, the placement works on the registers the count loaded.
+    constexpr int U = kRouteSteps;
     const int4* ids4 = (const int4*)a.topk_ids;
-    const int n4 = a.P / 4;
-    for (int i = tid; i < n4; i += 256) {
-        const int4 v = ids4[i];
-        if ((unsigned)v.x < (unsigned)a.E) atomicAdd(&hist[v.x], 1);
-        if ((unsigned)v.y < (unsigned)a.E) atomicAdd(&hist[v.y], 1);
-        if ((unsigned)v.z < (unsigned)a.E) atomicAdd(&hist[v.z], 1);
-        if ((unsigned)v.w < (unsigned)a.E) atomicAdd(&hist[v.w], 1);
-    }
-    for (int i = 4 * n4 + tid; i < a.P; i += 256) {
-        const int v = a.topk_ids[i];
-        if ((unsigned)v < (unsigned)a.E) atomicAdd(&hist[v], 1);
-    }
-    __syncthreads();
-    // ---- prefix sums over the experts before e (wave 0; E is small)
-    if (wave == 0) {
-        int off = 0, tiles = 0;
-        for (int i = lane; i < e; i += 64) {
-            const int c = hist[i];
-            off += c;
-            tiles += ((c + a.bm - 1) / a.bm) * a.tiles_n;
-        }
-        for (int sft = 32; sft > 0; sft >>= 1) {
-            off += __shfl_down(off, sft);
-            tiles += __shfl_down(tiles, sft);
-        }
-        if (lane == 0) { s_seg_lo = off; s_first = tiles; }
-    }
-    __syncthreads();
-    const int seg_lo = s_seg_lo, cnt = hist[e], seg_hi = seg_lo + cnt, first = s_first;
-    if (e == a.E - 1 && tid == 0) {
-        a.seg_off[a.E] = seg_hi;
-        const int total = first + ((cnt + a.bm - 1) / a.bm) * a.tiles_n;
-        *a.n_tiles_dev = total <= a.tab_capacity ? total : 0;   // the capacity is an upper bound by construction
-    }
-    if (tid == 0) a.seg_off[e] = seg_lo;
-
-    // ---- pass 2: stable placement, 1024 pairs per step (lane handles 4 consecutive pairs), U steps per pass of the
-    // loop: their ids are loaded together and their counts exchanged with one barrier, not one per step.
-    constexpr int U = 8;
-    int running = seg_lo;
-    for (int base0 = 0; base0 < a.P; base0 += 1024 * U) {
-      int vv[U][4];
+    const int lane_off = wave * (kChunk / kRouteWaves) + 4 * lane;      // + u * 256: offset of this lane's 4 pairs of step u
+    int vv[U][4];
+    auto load_chunk = [&](int base0) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int i0 = base0 + u * 1024 + 4 * tid;
-        if (i0 + 3 < a.P && (a.P & 3) == 0) {
-            const int4 q = ids4[i0 >> 2];
-            vv[u][0] = q.x; vv[u][1] = q.y; vv[u][2] = q.z; vv[u][3] = q.w;
-        } else {
+        for (int u = 0; u < U; ++u) {
+            const int i0 = base0 + lane_off + u * 256;
+            if (i0 + 3 < a.P) {                      // (i0 is a multiple of 4: the 16-byte load is aligned)
+                const int4 q = ids4[i0 >> 2];
+                vv[u][0] = q.x; vv[u][1] = q.y; vv[u][2] = q.z; vv[u][3] = q.w;
+            } else {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) vv[u][k] = i0 + k < a.P ? a.topk_ids[i0 + k] : -1;
-        }
-      }
-      // counts of this expert's pairs: per lane, then per wave, for all U steps; one barrier; then the positions
-      int mine[U], incl[U];
-      const int par = (base0 / (1024 * U)) & 1;       // wave_cnt is double-buffered over the passes of this loop
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        mine[u] = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) mine[u] += (vv[u][k] == e);
-        // inclusive prefix of `mine` over the wave, in lane order
-        incl[u] = mine[u];
-#pragma unroll
-        for (int sft = 1; sft < 64; sft <<= 1) {
-            const int t = __shfl_up(incl[u], sft);
-            if (lane >= sft) incl[u] += t;
-        }
-        if (lane == 63) wave_cnt[par][u][wave] = incl[u];
-      }
-      __syncthreads();
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int i0 = base0 + u * 1024 + 4 * tid;
-        int before = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const int c = wave_cnt[par][u][w];
-            if (w < wave) before += c;
-            total += c;
-        }
-        int pos = running + before + incl[u] - mine[u];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (vv[u][k] == e) {
-                if (a.pair_pos) a.pair_pos[i0 + k] = pos;
-                a.sorted_token[pos++] = (i0 + k) / a.topk;
-            } else if (e == 0 && a.pair_pos && i0 + k < a.P && (unsigned)vv[u][k] >= (unsigned)a.E) {
-                a.pair_pos[i0 + k] = -1;          // an id outside [0, E): the pair is nowhere in the sorted order
+                for (int k = 0; k < 4; ++k) vv[u][k] = i0 + k < a.P ? a.topk_ids[i0 + k] : -1;
             }
         }
-        running += total;
-      }
+    };
+    const bool one_chunk = a.P <= kChunk;
+    load_chunk(0);
+    if (tid == 0) {
+        s_tag = __hip_atomic_load(call_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+        s_e = (int)__hip_atomic_fetch_add(ticket_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    // ---- tile entries (they read sorted_token written above by this same workgroup)
+    __syncthreads();
+    const int e = s_e;
+    const unsigned tag = s_tag;
+    if (e >= a.E) {                                  // the ticket counter was not at zero: an earlier call never finished
+        if (tid == 0) *a.err = 1;
+        return;
+    }
+    // matches of this wave in front of this lane's pairs of step u (earlier steps, and lower lanes of step u);
+    // returns the wave's matches in the chunk (the same in every lane)
+    int before[U];
+    auto count_chunk = [&]() {
+        int wtot = 0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int b = wtot;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const unsigned long long m = __ballot(vv[u][k] == e);
+                b += __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                wtot += __popcll(m);
+            }
+            before[u] = b;
+        }
+        return wtot;
+    };
+    // ---- count this expert's pairs and publish the count
+    int wave_all = 0, wtot = 0;
+    for (int base0 = 0; base0 < a.P; base0 += kChunk) {
+        if (base0 > 0) load_chunk(base0);
+        wtot = count_chunk();
+        wave_all += wtot;
+    }
+    if (lane == 0) s_cnt[wave] = wave_all;
+    __syncthreads();
+    int cnt = 0;
+#pragma unroll
+    for (int w = 0; w < kRouteWaves; ++w) cnt += s_cnt[w];
+    if (tid == 0)
+        __hip_atomic_store(&counts[e], ((unsigned long long)tag << 32) | (unsigned)cnt, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+
+    // ---- stable placement, chunk by chunk
+    const bool in_lds = cnt <= kSegTokLds;
+    int seg_lo = 0, first = 0;
+    int running = 0;                                 // matches of the chunks before this one
+    int par = 0;                                     // wave_tot is double-buffered over the chunks
+    for (int base0 = 0; base0 < a.P || base0 == 0; base0 += kChunk, par ^= 1) {   // (once even without pairs)
+        if (!one_chunk) {
+            load_chunk(base0);
+            wtot = count_chunk();
+        }
+        if (lane == 0) wave_tot[par][wave] = wtot;
+        __syncthreads();
+        int wbase = 0, ctot = 0;
+#pragma unroll
+        for (int w = 0; w < kRouteWaves; ++w) {
+            const int c = wave_tot[par][w];
+            if (w < wave) wbase += c;
+            ctot += c;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int lp = wbase + before[u];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (vv[u][k] == e) cidx[lp++] = (unsigned short)(lane_off + u * 256 + k);
+        }
+        if (e == 0 && a.pair_pos) {
+            // an id outside [0, E): the pair is nowhere in the sorted order
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const int i = base0 + lane_off + u * 256 + k;
+                    if (i < a.P && (unsigned)vv[u][k] >= (unsigned)a.E) a.pair_pos[i] = -1;
+                }
+        }
+        if (base0 == 0 && wave == 0) {
+            // the counts of the experts before e: segment offset and first tile index
+            int off = 0, tiles = 0;
+            bool gave_up = false;
+            const long long t0 = wall_clock64();
+            for (int i = lane; i < e; i += 64) {
+                unsigned long long v;
+                for (;;) {
+                    v = __hip_atomic_load(&counts[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((unsigned)(v >> 32) == tag) break;
+                    if (wall_clock64() - t0 > a.wait_ticks) { gave_up = true; v = 0; break; }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                const int c = (int)(unsigned)v;
+                off += c;
+                tiles += ((c + a.bm - 1) / a.bm) * a.tiles_n;
+            }
+            for (int sft = 32; sft > 0; sft >>= 1) {
+                off += __shfl_down(off, sft);
+                tiles += __shfl_down(tiles, sft);
+            }
+            if (gave_up) *a.err = 1;
+            if (lane == 0) { s_seg_lo = off; s_first = tiles; }
+        }
+        __syncthreads();
+        if (base0 == 0) { seg_lo = s_seg_lo; first = s_first; }
+        for (int t = tid; t < ctot; t += kRouteThreads) {
+            const int i = base0 + cidx[t], tk = i / a.topk, pos = seg_lo + running + t;
+            a.sorted_token[pos] = tk;
+            if (a.pair_pos) a.pair_pos[i] = pos;
+            if (in_lds) seg_tok[running + t] = tk;
+        }
+        running += ctot;
+    }
+    const int seg_hi = seg_lo + cnt;
+    if (tid == 0) {
+        a.seg_off[e] = seg_lo;
+        if (e == a.E - 1) {
+            a.seg_off[a.E] = seg_hi;
+            const int total = first + ((cnt + a.bm - 1) / a.bm) * a.tiles_n;
+            *a.n_tiles_dev = total <= a.tab_capacity ? total : 0;   // the capacity is an upper bound by construction
+            // every workgroup has taken its ticket and read the call word by now (their counts are all in)
+            __hip_atomic_store(ticket_word, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(call_word, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    // ---- tile entries (they read this expert's sorted tokens: from LDS, or, for a longer segment, from sorted_token
+    // as this same workgroup wrote it above)
     __threadfence_block();
     __syncthreads();
+    auto tok_at = [&](int pos) { return in_lds ? seg_tok[pos - seg_lo] : a.sorted_token[pos]; };
     const int mt = (cnt + a.bm - 1) / a.bm;
     if (first + mt * a.tiles_n > a.tab_capacity) return;
-    for (int k = tid; k < mt * a.tiles_n; k += 256) {
+    for (int k = tid; k < mt * a.tiles_n; k += kRouteThreads) {
         const int n = k / mt, m = k - n * mt;
         MoeTile t;
         t.expert = e;
@@ -131,7 +201,7 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
         t.m_end = min(t.m0 + a.bm, seg_hi);
         t.n_tile = n;
         // tokens rise inside a segment: the first and last token bound the rows of T this tile reads
-        const int tok_lo = a.sorted_token[t.m0], tok_hi = a.sorted_token[t.m_end - 1];
+        const int tok_lo = tok_at(t.m0), tok_hi = tok_at(t.m_end - 1);
         t.f_lo = min(tok_lo / a.rows_per_flag, a.n_flags - 1);
         t.f_hi = min(tok_hi / a.rows_per_flag, a.n_flags - 1);
         t.st_lo = t.m0;
@@ -142,7 +212,7 @@ __global__ __launch_bounds__(256) void moe_route_kernel(const MoeRouteArgs a)
                 int lo = t.m0, hi = t.m_end;
                 while (lo < hi) {
                     const int mid = (lo + hi) >> 1;
-                    if (a.sorted_token[mid] < tok) lo = mid + 1; else hi = mid;
+                    if (tok_at(mid) < tok) lo = mid + 1; else hi = mid;
                 }
                 return lo;
             };
@@ -191,8 +261,8 @@ hipError_t launch_topk_reduce(const TopkReduceArgs& a, int n_workgroups, hipStre
 
 hipError_t launch_moe_route(const MoeRouteArgs& a, hipStream_t stream)
 {
-    if (a.E > kMaxExperts) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(moe_route_kernel, dim3(a.E), dim3(256), (size_t)a.E * sizeof(int), stream, a);
+    if (a.E > kMoeMaxExperts || !a.ctrl || !a.err) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(moe_route_kernel, dim3(a.E), dim3(kRouteThreads), 0, stream, a);
     return hipGetLastError();
 }
 

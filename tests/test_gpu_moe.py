@@ -139,6 +139,25 @@ def test_moe_segments_with_full_blocks_and_short_tails(tile):
         run.close()
 
 
+@pytest.mark.parametrize("W,tpr,E,topk", [(2, 4600, 2, 2), (3, 5463, 3, 1)])
+def test_moe_long_segments_and_more_pairs_than_one_pass_of_the_routing_holds(W, tpr, E, topk):
+    # 18400 pairs (a multiple of four) and 16389 (not one): more than the 16384 ids the routing kernel takes at a time,
+    # and segments of more than 4096 rows (longer than what it keeps on chip for the tile table).  Integer inputs: exact.
+    sh = wl.MoeShape("moe_long", 21, W, tpr, 64, 64, E, topk)
+    inp = wl.make_moe(sh, x_dist=("int", 2), w_dist=("int", 2))
+    want = oracle.moe_gemm(inp.shards, inp.W_ekn, inp.topk_ids, 0)
+    tok_ref, _, seg_ref = oracle.moe_route(inp.topk_ids, sh.E)
+    assert np.diff(seg_ref).max() > 4096 and sh.T * sh.topk > 16384
+    run = MoeRun(inp, 0)
+    try:
+        Y, tok, seg = run.run()
+        assert np.array_equal(tok, tok_ref)
+        assert np.array_equal(seg.astype(np.int64), seg_ref)
+        assert np.array_equal(Y.cpu().numpy().astype(np.float64), want)
+    finally:
+        run.close()
+
+
 def test_moe_empty_experts_skewed_routing_and_invalid_ids():
     sh = wl.MoeShape("moe_skew", 9, 2, 40, 64, 40, 7, 2)
     inp = wl.make_moe(sh)

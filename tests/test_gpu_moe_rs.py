@@ -136,6 +136,22 @@ def test_moe_rs_three_experts_per_token():
         run.close()
 
 
+def test_moe_rs_long_segments_exact():
+    # every token goes to both experts: segments of 9200 rows, 18400 pairs; without Z_other only the rows of this
+    # rank's tokens are computed (one run of rows in the middle of each segment)
+    sh = wl.MoeRsShape("moe_rs_long", 22, 2, 4600, 64, 64, 2, 2)
+    inp = wl.make_moe_rs(sh, rank=1, h_dist=("int", 2), w_dist=("int", 2), slot_dist=("int", 3))
+    inp.gate[:] = np.float32(0.5)
+    want = oracle.moe_rs(inp.H, inp.W2_ekn, inp.topk_ids, inp.gate, inp.peer_slots, sh.W, 1)
+    run = MoeRsRun(inp, 1)
+    try:
+        for with_other in (False, True):
+            R, _ = run.run(True, with_other=with_other)
+            assert np.array_equal(R.cpu().numpy().astype(np.float64), want)
+    finally:
+        run.close()
+
+
 @pytest.mark.parametrize("chunks", [1, 4])
 def test_moe_rs_integer_inputs_exact(chunks):
     sh = wl.MoeRsShape("moe_rs_int", 18, 2, 40, 128, 40, 7, 2)
