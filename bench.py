@@ -653,26 +653,38 @@ def main() -> int:
         agg.agg_reserve_moe(qctx, mr.T, mr.topk, mr.E, mr.N)
         qp, qc = qctx.streams()
 
-        def step_moe_rs():
+        Zo = torch.empty((mr.T, mr.N), device="cuda", dtype=torch.float32)
+
+        def step_moe_rs(z_other=Zo):
             agg.signal_reset(qctx)
             for w in range(1, mr.W):
                 agg.signal_set(qctx, w, qc)
-            agg.moe_rs(qctx, mr.T, mr.topk, mr.E, mr.N, mr.Kl, Hh, W2, ids2, g2, Yw, tk2, sg2, pp2, sl2, None, R2, mr.N,
+            agg.moe_rs(qctx, mr.T, mr.topk, mr.E, mr.N, mr.Kl, Hh, W2, ids2, g2, Yw, tk2, sg2, pp2, sl2, z_other, R2, mr.N,
                        agg.F32, qp, qc)
 
+        # A rank of the real operation computes its K slice's partial sums for EVERY token and pushes seven eighths of
+        # them to their owners: here they land in Z_other.  That is the step that is reported; the variant that
+        # computes this rank's own tokens only (Z_other left out) is an eighth of that work and is listed beside it.
         t_mrs = timed(step_moe_rs, 50, 100)
+        t_own = timed(lambda: step_moe_rs(None), 50, 50)
         assert agg.agg_status(qctx) == agg.OK
         qctx.free()
-        # bytes that must move whatever the implementation: H and the weights once, the W slots read, R written.  The
-        # fp32 intermediate Y (written by the grouped GEMM, read by the top-k reduction) is this implementation's own
-        # round trip, not compulsory traffic: it is reported beside, not counted
-        mrs_bytes = (Pr * mr.Kl * 2 + mr.E * mr.N * mr.Kl * 2 + (mr.W + 1) * mr.tokens_per_rank * mr.N * 4)
+        # bytes that must move whatever the implementation: H and the weights once, the partial sums of the other
+        # ranks' tokens written once (the pushes), the W slots read, R written.  The fp32 intermediate Y (written by the
+        # grouped GEMM, read by the top-k reduction) is this implementation's own round trip, not compulsory traffic:
+        # it is reported beside, not counted
+        mrs_bytes = (Pr * mr.Kl * 2 + mr.E * mr.N * mr.Kl * 2 + (mr.T - mr.tokens_per_rank) * mr.N * 4
+                     + (mr.W + 1) * mr.tokens_per_rank * mr.N * 4)
         out["moe_rs"] = {"workload": mr.name, "ms": round(t_mrs * 1e3, 4), "tflops": round(mr.flops / t_mrs / 1e12, 1),
                          "compulsory_bytes": mrs_bytes,
                          "compulsory_GBps": round(mrs_bytes / t_mrs / 1e9, 1),
                          "frac_of_hbm_peak": round(mrs_bytes / t_mrs / 1e9 / PEAK_HBM_GBPS, 4),
                          "intermediate_Y_round_trip_bytes": 2 * Pr * mr.N * 4,
-                         "note": "routing + grouped GEMM (K = 192 per rank) + top-k reduction + reducer, per step"}
+                         "ms_own_tokens_only": round(t_own * 1e3, 4),
+                         "note": "routing + grouped GEMM (K = 192 per rank, all tokens) + top-k reduction (all tokens; the "
+                                 "other ranks' partial sums go to Z_other) + reducer, per step; ms_own_tokens_only = the "
+                                 "same call without Z_other (an eighth of the GEMM's rows stored and reduced)"}
+        del Zo
         del Hh, W2, Yw, sl2
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of rows of the same workload

@@ -288,7 +288,7 @@ int agg_reserve_moe(agg_ctx* ctx, int Ttok, int topk, int E, int N);
 /*
  * ag_moe_gemm for callers that cannot allocate device memory and cannot ask a context to (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the routing's
- * counters and the tile table live in a fixed array of 1056 KiB in the library's own device image (one copy per GPU,
+ * counters and the tile table live in a fixed array of 1088 KiB in the library's own device image (one copy per GPU,
  * held until the process ends) instead of a reserved workspace.  The call allocates nothing, frees nothing and does
  * not synchronise.  It returns AGG_ERR_UNSUPPORTED_SHAPE when the table of the problem could exceed the array:
  * (Ttok * topk / 128 + E) * ceil(N / 128) entries of 32 bytes must fit in 32760 entries (the Table 4 shape needs

@@ -57,8 +57,8 @@ struct GemmParams {
 };
 
 // One output tile of the grouped GEMM: rows [m0, m_end) of the sorted pair list (inside one expert's segment),
-// columns of n-tile n_tile, waiting for signals f_lo..f_hi; of its rows, [st_lo, st_hi) are stored (all of them,
-// unless the caller wants the rows of one token range only; an empty range = the tile is skipped).
+// columns of n-tile n_tile, waiting for signals f_lo..f_hi; of its rows, [st_lo, st_hi) are stored (the routing
+// kernel lists all of them; an empty range = the tile is skipped).
 struct MoeTile {
     int expert, m0, m_end, n_tile, f_lo, f_hi, st_lo, st_hi;
 };
@@ -80,10 +80,11 @@ struct MoeRouteArgs {
     int* err;                     // device word: set to 1 when that wait is given up
 };
 // Control block of the MoE routing: the tile count (int, read by the grouped GEMM), the number of finished routing
-// calls, the ticket counter, and one tagged count per expert.
+// calls, the ticket counter, and two tagged counts per expert (its pairs; those of them that get tiles).
 constexpr int kMoeMaxExperts = 4096;
 constexpr size_t kMoeCtrlCall = 8, kMoeCtrlTicket = 16, kMoeCtrlCounts = 256;
-constexpr size_t kMoeCtrlBytes = kMoeCtrlCounts + (size_t)kMoeMaxExperts * 8;
+constexpr size_t kMoeCtrlKept = kMoeCtrlCounts + (size_t)kMoeMaxExperts * 8;
+constexpr size_t kMoeCtrlBytes = kMoeCtrlKept + (size_t)kMoeMaxExperts * 8;
 hipError_t launch_moe_route(const MoeRouteArgs& a, hipStream_t stream);
 
 // Top-k reduction of MoE + ReduceScatter: Z[t, :] = sum_s gate[t, s] * Y[pair_pos[t * topk + s], :]

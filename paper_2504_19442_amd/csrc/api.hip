@@ -108,7 +108,7 @@ int resolve_b(agg_ctx* c, const void* B, int ldb, int b_layout, int N, int K, hi
 // address: the device address is looked up once per context (symm_alloc, with the context's device current).
 constexpr size_t kStaticTabOffset = kMoeCtrlBytes;         // the routing's control block first, the table after it
 constexpr size_t kStaticTabEntries = 32760;
-constexpr size_t kStaticScratchBytes = kStaticTabOffset + kStaticTabEntries * sizeof(MoeTile);   // 1056 KiB
+constexpr size_t kStaticScratchBytes = kStaticTabOffset + kStaticTabEntries * sizeof(MoeTile);   // 1088 KiB
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 // Upper bound of the grouped GEMM's tile table over all tile configurations: sum over experts of
@@ -804,7 +804,8 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
 // (A = the routed rows themselves, nothing to wait for).
 // The routing's control block (its first word is the tile count) and the tile table come from the caller of this
 // function: the context's reserved buffers, or the library's static scratch.
-// keep_lo < keep_hi: only the rows of tokens in [keep_lo, keep_hi) are wanted; tiles without such rows are skipped.
+// keep_lo < keep_hi: only the rows of tokens in [keep_lo, keep_hi) are wanted: the routing lists tiles for those rows only
+// (one run of rows per expert, since tokens rise inside a segment).
 static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, const int32_t* topk_ids, const void* A,
                         bool gathered, const void* weights, int32_t* sorted_token, int32_t* seg_off, int32_t* pair_pos,
                         void* Y, int ldy, int y_dtype, hipStream_t stream, int* n_tiles_word, MoeTile* tab, long long tab_cap,
@@ -825,7 +826,8 @@ static int grouped_gemm(agg_ctx* c, int Ttok, int topk, int E, int N, int K, con
     if (cfg < 0) {
         const int cand[3] = {TILE_256x224, TILE_256x256, TILE_128x128};
         const double eff[3] = {1.0, 1.0, 0.6};
-        const double rows = 1.15 * (double)P / E;
+        // (with a token range to keep, only the rows of those tokens get tiles)
+        const double rows = 1.15 * (keep_lo < keep_hi ? (double)(keep_hi - keep_lo) * topk : (double)P) / E;
         double best = 1e300;
         for (int i = 0; i < 3; ++i) {
             const TileShape ts = tile_shape(cand[i]);

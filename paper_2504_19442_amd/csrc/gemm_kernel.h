@@ -619,6 +619,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                 // a whole number of chunks (always so for a full tile)
                 const bool fast = p.c_vec_ok && (n_valid * esz) % 16 == 0;
                 const int cpr_valid = n_valid * esz / 16;
+                if constexpr (MF == 16 && esz == 4) {
+                    if (fast) {
+                        // fp32 output from 16x16 blocks: the four values a lane holds of a block are 16 consecutive
+                        // bytes of an output row, and the four lanes that share a row cover 64 consecutive bytes --
+                        // whole 64-byte sectors per store, so the values go from the registers straight to memory
+                        // (neighbouring column blocks, stored back to back, complete the 128-byte lines in L2)
+                        const int colq = 4 * (lane_e >> 4);
+                        static_for<C_::MB16>([&](auto i_c) {
+                            constexpr int i = decltype(i_c)::value;
+                            char* dst = row_ptr(row_w + i * 16 + (lane_e & 15), esz);
+                            if (dst) {
+                                T* q = (T*)dst + colq;
+                                static_for<C_::NB16>([&](auto j_c) {
+                                    constexpr int j = decltype(j_c)::value;
+                                    constexpr int r0 = (i * C_::NB16 + j) * 4;
+                                    const float x0 = acc_read<r0>(), x1 = acc_read<r0 + 1>(), x2 = acc_read<r0 + 2>(),
+                                                x3 = acc_read<r0 + 3>();
+                                    if (n_valid == BN || colq + j * 16 < n_valid)
+                                        __builtin_nontemporal_store(Tx4{x0, x1, x2, x3}, (Tx4*)(q + j * 16));
+                                });
+                            }
+                        });
+                        return;
+                    }
+                }
                 if (fast) {
                     // stage 32 rows x BN columns per pass in this wave's own part of LDS, then move whole
                     // 16-byte chunks of rows to C: full cache lines per store instruction

@@ -31,13 +31,19 @@ constexpr int kChunk = kRouteWaves * kRouteSteps * 256;     // pairs taken at a 
 __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRouteArgs a)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    __shared__ int s_e, s_cnt[kRouteWaves], wave_tot[2][kRouteWaves], s_seg_lo, s_first;
+    __shared__ int s_e, s_cnt[kRouteWaves], s_below[2][kRouteWaves], wave_tot[2][kRouteWaves], s_seg_lo, s_first;
     __shared__ unsigned s_tag;
     __shared__ int seg_tok[kSegTokLds];           // this expert's tokens in sorted order, while they fit
     __shared__ unsigned short cidx[kChunk];       // the chunk's matching pairs (offset inside the chunk), in order
     unsigned* const call_word = (unsigned*)(a.ctrl + kMoeCtrlCall);
     unsigned* const ticket_word = (unsigned*)(a.ctrl + kMoeCtrlTicket);
     unsigned long long* const counts = (unsigned long long*)(a.ctrl + kMoeCtrlCounts);
+    unsigned long long* const kept = (unsigned long long*)(a.ctrl + kMoeCtrlKept);
+    // keep_lo < keep_hi: only the rows of tokens in [keep_lo, keep_hi) get tiles.  Tokens rise inside a segment, so
+    // they are one run of its rows: from the number of the expert's pairs below flat pair index keep_lo * topk to the
+    // number below keep_hi * topk.
+    const bool keep = a.keep_lo < a.keep_hi;
+    const int x_lo = keep ? a.keep_lo * a.topk : 0, x_hi = keep ? a.keep_hi * a.topk : 0;
     // All loads of a chunk are issued before the first use: one memory latency per chunk.  When all pairs fit one
     // chunk, the placement works on the registers the count loaded.
     constexpr int U = kRouteSteps;
@@ -73,16 +79,23 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
     // matches of this wave in front of this lane's pairs of step u (earlier steps, and lower lanes of step u);
     // returns the wave's matches in the chunk (the same in every lane)
     int before[U];
-    auto count_chunk = [&]() {
+    int below_lo = 0, below_hi = 0;                  // the wave's matches below x_lo / x_hi, over all chunks counted
+    auto count_chunk = [&](int base0, bool with_bounds) {
         int wtot = 0;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int b = wtot;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const unsigned long long m = __ballot(vv[u][k] == e);
+                const bool hit = vv[u][k] == e;
+                const unsigned long long m = __ballot(hit);
                 b += __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
                 wtot += __popcll(m);
+                if (with_bounds) {
+                    const int i = base0 + lane_off + u * 256 + k;
+                    below_lo += __popcll(__ballot(hit && i < x_lo));
+                    below_hi += __popcll(__ballot(hit && i < x_hi));
+                }
             }
             before[u] = b;
         }
@@ -92,17 +105,22 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
     int wave_all = 0, wtot = 0;
     for (int base0 = 0; base0 < a.P; base0 += kChunk) {
         if (base0 > 0) load_chunk(base0);
-        wtot = count_chunk();
+        wtot = count_chunk(base0, keep);
         wave_all += wtot;
     }
-    if (lane == 0) s_cnt[wave] = wave_all;
+    if (lane == 0) { s_cnt[wave] = wave_all; s_below[0][wave] = below_lo; s_below[1][wave] = below_hi; }
     __syncthreads();
-    int cnt = 0;
+    int cnt = 0, lo_cnt = 0, hi_cnt = 0;
 #pragma unroll
-    for (int w = 0; w < kRouteWaves; ++w) cnt += s_cnt[w];
-    if (tid == 0)
+    for (int w = 0; w < kRouteWaves; ++w) { cnt += s_cnt[w]; lo_cnt += s_below[0][w]; hi_cnt += s_below[1][w]; }
+    const int tiled = keep ? hi_cnt - lo_cnt : cnt;  // rows of this expert that get tiles
+    if (tid == 0) {
         __hip_atomic_store(&counts[e], ((unsigned long long)tag << 32) | (unsigned)cnt, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
+        if (keep)
+            __hip_atomic_store(&kept[e], ((unsigned long long)tag << 32) | (unsigned)tiled, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+    }
 
     // ---- stable placement, chunk by chunk
     const bool in_lds = cnt <= kSegTokLds;
@@ -112,7 +130,7 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
     for (int base0 = 0; base0 < a.P || base0 == 0; base0 += kChunk, par ^= 1) {   // (once even without pairs)
         if (!one_chunk) {
             load_chunk(base0);
-            wtot = count_chunk();
+            wtot = count_chunk(base0, false);
         }
         if (lane == 0) wave_tot[par][wave] = wtot;
         __syncthreads();
@@ -145,17 +163,19 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
             int off = 0, tiles = 0;
             bool gave_up = false;
             const long long t0 = wall_clock64();
-            for (int i = lane; i < e; i += 64) {
-                unsigned long long v;
+            auto wait_for = [&](const unsigned long long* word) {
                 for (;;) {
-                    v = __hip_atomic_load(&counts[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if ((unsigned)(v >> 32) == tag) break;
-                    if (wall_clock64() - t0 > a.wait_ticks) { gave_up = true; v = 0; break; }
+                    const unsigned long long v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((unsigned)(v >> 32) == tag) return (int)(unsigned)v;
+                    if (wall_clock64() - t0 > a.wait_ticks) { gave_up = true; return 0; }
                     __builtin_amdgcn_s_sleep(1);
                 }
-                const int c = (int)(unsigned)v;
+            };
+            for (int i = lane; i < e; i += 64) {
+                const int c = wait_for(&counts[i]);
+                const int r = keep ? wait_for(&kept[i]) : c;
                 off += c;
-                tiles += ((c + a.bm - 1) / a.bm) * a.tiles_n;
+                tiles += ((r + a.bm - 1) / a.bm) * a.tiles_n;
             }
             for (int sft = 32; sft > 0; sft >>= 1) {
                 off += __shfl_down(off, sft);
@@ -179,7 +199,7 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
         a.seg_off[e] = seg_lo;
         if (e == a.E - 1) {
             a.seg_off[a.E] = seg_hi;
-            const int total = first + ((cnt + a.bm - 1) / a.bm) * a.tiles_n;
+            const int total = first + ((tiled + a.bm - 1) / a.bm) * a.tiles_n;
             *a.n_tiles_dev = total <= a.tab_capacity ? total : 0;   // the capacity is an upper bound by construction
             // every workgroup has taken its ticket and read the call word by now (their counts are all in)
             __hip_atomic_store(ticket_word, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -191,14 +211,15 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
     __threadfence_block();
     __syncthreads();
     auto tok_at = [&](int pos) { return in_lds ? seg_tok[pos - seg_lo] : a.sorted_token[pos]; };
-    const int mt = (cnt + a.bm - 1) / a.bm;
+    const int row_lo = keep ? seg_lo + lo_cnt : seg_lo, row_hi = row_lo + tiled;
+    const int mt = (tiled + a.bm - 1) / a.bm;
     if (first + mt * a.tiles_n > a.tab_capacity) return;
     for (int k = tid; k < mt * a.tiles_n; k += kRouteThreads) {
         const int n = k / mt, m = k - n * mt;
         MoeTile t;
         t.expert = e;
-        t.m0 = seg_lo + m * a.bm;
-        t.m_end = min(t.m0 + a.bm, seg_hi);
+        t.m0 = row_lo + m * a.bm;
+        t.m_end = min(t.m0 + a.bm, row_hi);
         t.n_tile = n;
         // tokens rise inside a segment: the first and last token bound the rows of T this tile reads
         const int tok_lo = tok_at(t.m0), tok_hi = tok_at(t.m_end - 1);
@@ -206,19 +227,6 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
         t.f_hi = min(tok_hi / a.rows_per_flag, a.n_flags - 1);
         t.st_lo = t.m0;
         t.st_hi = t.m_end;
-        if (a.keep_lo < a.keep_hi) {
-            // tokens rise inside the segment: the rows of tokens in [keep_lo, keep_hi) are one run of the tile's rows
-            auto first_not_below = [&](int tok) {
-                int lo = t.m0, hi = t.m_end;
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    if (tok_at(mid) < tok) lo = mid + 1; else hi = mid;
-                }
-                return lo;
-            };
-            t.st_lo = first_not_below(a.keep_lo);
-            t.st_hi = first_not_below(a.keep_hi);
-        }
         a.tile_tab[first + k] = t;
     }
 }
