@@ -637,7 +637,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_vgpr(192))) void gem
                                     const float x0 = acc_read<r0>(), x1 = acc_read<r0 + 1>(), x2 = acc_read<r0 + 2>(),
                                                 x3 = acc_read<r0 + 3>();
                                     if (n_valid == BN || colq + j * 16 < n_valid)
-                                        __builtin_nontemporal_store(Tx4{x0, x1, x2, x3}, (Tx4*)(q + j * 16));
+                                        __builtin_nontemporal_store(Tx4{(T)x0, (T)x1, (T)x2, (T)x3}, (Tx4*)(q + j * 16));
                                 });
                             }
                         });
