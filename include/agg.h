@@ -13,8 +13,9 @@
  * effect when it fails; agg_strerror names a code.  Functions are not thread-safe
  * on one context; different contexts are independent.  A context carries one set of
  * arrival counters, slice counters and tile tables: two producers, two gemm_rs /
- * gemm_rs_scatter, two ag_moe_gemm launches or two GEMMs with an AGG_B_KN operand of ONE context must not
- * be in flight at the same time (order them on a stream or with events, or use a context each).
+ * gemm_rs_scatter or two ag_moe_gemm launches of ONE context must not be in flight at the same time (order
+ * them on a stream or with events, or use a context each); GEMMs with an AGG_B_KN operand share one buffer of
+ * the context and are ordered by the library itself.
  *
  * Vocabulary (the paper's, Section 2.1 and Algorithms 1-3): W = WORLD_SIZE,
  * rank = RANK, T = symmetric buffer, S = signal array, L = a rank's local shard.
@@ -49,8 +50,9 @@ enum { AGG_B_NK = 0,                         /* B stored [N][K], K contiguous (w
        AGG_B_KN = 1 };                       /* B stored [K][N], N contiguous: transposed into a buffer of the context
                                                 on the GEMM's stream before every GEMM (one more pass over B; the
                                                 buffer is sized by agg_reserve_b_kn beforehand; calls with this
-                                                layout on one context share it, so they must be ordered on one
-                                                stream or with events); ldb >= N */
+                                                layout on one context share it: a call on another stream than the
+                                                previous one is made to wait, on the device, for that one's GEMM);
+                                                ldb >= N */
 enum { AGG_PRODUCER_KERNEL = 0,              /* copy kernel on a few CUs, release-stores the signals */
        AGG_PRODUCER_SDMA = 1,               /* copy engine (no compute units) + one 4-byte copy per signal */
        AGG_PRODUCER_LINKS = 2,              /* full mesh: every peer's shard on a "link" of its own, all at once, chunk by chunk */

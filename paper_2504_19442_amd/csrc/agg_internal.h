@@ -194,6 +194,9 @@ struct agg_ctx {
     int moe_tab_cap;
     uint16_t* b_nk;       // [N][K] copy of a B that was given as [K][N] (sized by agg_reserve_b_kn)
     size_t b_nk_elems;
+    hipEvent_t b_nk_free;     // recorded behind the last GEMM that read b_nk, on b_nk_stream
+    hipStream_t b_nk_stream;
+    int b_nk_in_use;
     unsigned char* static_scratch;   // device address of the library's static scratch array on this context's GPU
     int can_wait_value;  // the device supports stream waits on a memory word
     hipEvent_t gemm_done; // GEMM-RS: orders the reducer after the GEMM where it does not

@@ -97,9 +97,22 @@ int resolve_b(agg_ctx* c, const void* B, int ldb, int b_layout, int N, int K, hi
         return AGG_OK;
     }
     if (c->b_nk_elems < (size_t)N * K) return AGG_ERR_NOT_RESERVED;
+    // the buffer is one per context: a call on another stream than the last one that used it first waits (on the
+    // device) for that one's GEMM, so that two such calls can never read each other's transposed B
+    if (c->b_nk_in_use && stream != c->b_nk_stream) HIP_TRY(hipStreamWaitEvent(stream, c->b_nk_free, 0));
     HIP_TRY(launch_transpose_kn((const uint16_t*)B, ldb, K, N, c->b_nk, stream));
     *B_nk = c->b_nk;
     *ld_nk = K;
+    return AGG_OK;
+}
+
+// After the launch of a GEMM that reads the context's transposed copy of B: mark where the buffer becomes free again.
+int b_kn_launched(agg_ctx* c, int b_layout, hipStream_t stream)
+{
+    if (b_layout != AGG_B_KN) return AGG_OK;
+    HIP_TRY(hipEventRecord(c->b_nk_free, stream));
+    c->b_nk_stream = stream;
+    c->b_nk_in_use = 1;
     return AGG_OK;
 }
 
@@ -195,6 +208,7 @@ int symm_alloc(agg_ctx** out, int world_size, int rank, size_t shard_bytes, int 
     if ((rc = hip_fail(hipStreamCreateWithFlags(&c->consumer_stream, hipStreamNonBlocking))) != AGG_OK) goto fail;
     if ((rc = pick_concurrent_stream(c)) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipEventCreateWithFlags(&c->gemm_done, hipEventDisableTiming))) != AGG_OK) goto fail;
+    if ((rc = hip_fail(hipEventCreateWithFlags(&c->b_nk_free, hipEventDisableTiming))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipGetSymbolAddress((void**)&c->static_scratch, HIP_SYMBOL(scratch)))) != AGG_OK) goto fail;
     if ((rc = hip_fail(hipDeviceSynchronize())) != AGG_OK) goto fail;
     *out = c;
@@ -211,6 +225,7 @@ int symm_free(agg_ctx* c)
     if (c->producer_stream) (void)hipStreamDestroy(c->producer_stream);
     if (c->consumer_stream) (void)hipStreamDestroy(c->consumer_stream);
     if (c->gemm_done) (void)hipEventDestroy(c->gemm_done);
+    if (c->b_nk_free) (void)hipEventDestroy(c->b_nk_free);
     if (c->b_nk) (void)hipFree(c->b_nk);
     if (c->moe_ws) (void)hipFree(c->moe_ws);
     if (c->moe_tab) (void)hipFree(c->moe_tab);
@@ -517,7 +532,8 @@ int ag_gemm(agg_ctx* c, int M, int N, int K, const void* B, int ldb, int b_layou
     p.err = c->err;
     const long long tiles = (long long)p.tiles_m * p.tiles_n;
     const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
-    return hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)consumer_stream));
+    if ((rc = hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)consumer_stream))) != AGG_OK) return rc;
+    return b_kn_launched(c, b_layout, (hipStream_t)consumer_stream);
 }
 
 static int reduce_impl(agg_ctx* c, int Ms, int N, const float* const* slots, void* R, int ldr, int r_dtype, int n_workgroups,
@@ -709,7 +725,8 @@ int gemm_rs_scatter(agg_ctx* c, int M, int N, int Kl, const void* A_local, int l
     fill_schedule(p, cfg, Ms, first_slice * Ms);
     const long long tiles = (long long)p.tiles_m * p.tiles_n;
     const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
-    return hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)gemm_stream));
+    if ((rc = hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)gemm_stream))) != AGG_OK) return rc;
+    return b_kn_launched(c, b_layout, (hipStream_t)gemm_stream);
 }
 
 int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, const void* B_local, int ldb, int b_layout,
@@ -773,6 +790,7 @@ int gemm_rs(agg_ctx* c, int M, int N, int Kl, const void* A_local, int lda, cons
         const long long tiles = (long long)p.tiles_m * p.tiles_n;
         const int grid = (int)(tiles < c->num_cus ? tiles : c->num_cus);
         rc = hip_fail(launch_gemm(p, cfg, grid, (hipStream_t)gemm_stream));
+        if (rc == AGG_OK) rc = b_kn_launched(c, b_layout, (hipStream_t)gemm_stream);
     }
     if (rc != AGG_OK) return rc;
     // The reducer waits for this rank's own slot, which the GEMM above produces.  A reducer that spun for that

@@ -485,6 +485,38 @@ def test_b_given_as_k_by_n_is_transposed_first_same_bits():
         run.close()
 
 
+def test_two_k_by_n_calls_on_two_streams_do_not_mix_their_operands():
+    # one transposed copy per context: a second [K][N] call on another stream, with another B, must wait for the
+    # first one's GEMM (the library orders them); both results are those of the [N][K] calls
+    inp = wl.make_ag_gemm(wl.AG_RAGGED)
+    sh = wl.AG_RAGGED
+    run = AgGemmRun(inp, 1)
+    try:
+        agg.agg_reserve_b_kn(run.ctx, sh.N, sh.K)
+        B1_kn = dev_bf16(inp.B_kn)
+        neg = (inp.B_kn ^ np.uint16(0x8000)).astype(np.uint16)            # -B: same magnitudes, every sign flipped
+        B2_kn = dev_bf16(neg)
+        B2_nk = dev_bf16(np.ascontiguousarray(neg.T))
+        run.run(tile=1)                                                    # T filled, signals of this epoch set
+        ref1 = torch.empty((sh.M, sh.N), device="cuda", dtype=torch.float32)
+        ref2 = torch.empty_like(ref1)
+        agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, run.B_nk, sh.K, agg.B_NK, ref1, sh.N, agg.F32, run.cons)
+        agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, B2_nk, sh.K, agg.B_NK, ref2, sh.N, agg.F32, run.cons)
+        torch.cuda.synchronize()
+        assert not torch.equal(ref1, ref2) and torch.allclose(ref2, -ref1, rtol=1e-3, atol=1e-3)
+        for _ in range(3):
+            C1 = torch.full((sh.M, sh.N), float("nan"), device="cuda", dtype=torch.float32)
+            C2 = torch.full((sh.M, sh.N), float("nan"), device="cuda", dtype=torch.float32)
+            torch.cuda.synchronize()
+            agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, B1_kn, sh.N, agg.B_KN, C1, sh.N, agg.F32, run.cons)
+            agg.ag_gemm(run.ctx, sh.M, sh.N, sh.K, B2_kn, sh.N, agg.B_KN, C2, sh.N, agg.F32, run.prod)
+            torch.cuda.synchronize()
+            assert agg.agg_status(run.ctx) == agg.OK
+            assert torch.equal(C1, ref1) and torch.equal(C2, ref2)
+    finally:
+        run.close()
+
+
 def test_seeded_random_shapes_and_settings_exact():
     """Thirty seeded combinations of world size, shard rows, K, N, signals per shard, tile shape, tile order, producer,
     own-shard handling, output type and launch order; integer inputs, so every result must equal the oracle exactly."""
