@@ -281,8 +281,11 @@ int ag_moe_gemm(agg_ctx* ctx, int Ttok, int topk, int E, int N, int K,
  * allocate device memory (they synchronise the device; they only ever grow a workspace).  No GEMM, MoE or reducer call
  * allocates or synchronises: one that finds its workspace missing or too small returns AGG_ERR_NOT_RESERVED.
  *   agg_reserve_b_kn: the [N][K] copy of a B operand given as AGG_B_KN (ag_gemm, gemm_rs, gemm_rs_scatter).
- *   agg_reserve_moe : the tile count and tile table of the grouped GEMM (ag_moe_gemm, moe_rs) for problems of up to
- *                     Ttok * topk pairs, E experts and N columns, whatever tile configuration is chosen later.
+ *   agg_reserve_moe : the routing's counters (66 KB, zeroed once) and the tile table of the grouped GEMM (ag_moe_gemm,
+ *                     moe_rs) for problems of up to Ttok * topk pairs, E experts and N columns, whatever tile
+ *                     configuration is chosen later.  The routing kernel's workgroups read one another's counts through
+ *                     those counters and wait for them (bounded by the limit of agg_set_wait_limit_us, like every wait): a MoE
+ *                     call is one launch of E workgroups of 1024 threads that all have to become resident in turn.
  */
 int agg_reserve_b_kn(agg_ctx* ctx, int N, int K);
 int agg_reserve_moe(agg_ctx* ctx, int Ttok, int topk, int E, int N);
