@@ -233,31 +233,58 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
 
 // Top-k reduction (Section 4.1, "MoE ReduceScatter", the step between the grouped GEMM and the reduce scatter):
 // every token's `topk` rows of Y are weighted with its gate values and summed in slot order, fp32, starting from the
-// first product.  Streaming: one float4 per lane, tokens of this rank first (their slice is what the reducer waits for).
+// first product.  Streaming, one float4 column chunk per lane, tokens of this rank first (their slice is what the
+// reducer waits for).  A lane works on U tokens at a time: the row of a pair is found through pair_pos, so every
+// product is two loads in a row (index, then data); with U tokens in hand the U indices are in flight together and
+// then the U rows, instead of one such chain after the other.
 __global__ __launch_bounds__(256) void topk_reduce_kernel(const TopkReduceArgs a)
 {
     typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+    constexpr int U = 4;
     const int n4 = a.N / 4;
-    const long long total = (long long)a.T * n4;
     const int own_n = a.own_hi - a.own_lo;
+    const int n_tok = a.Z_other ? a.T : own_n;                 // tokens that are reduced: own first, then the others
+    const long long total = (long long)((n_tok + U - 1) / U) * n4;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
-        int v = (int)(i / n4);                       // place in the order: own tokens first, then the others
-        const int j = (int)(i - (long long)v * n4);
-        int t;
-        if (v < own_n) t = a.own_lo + v;
-        else { t = v - own_n; if (t >= a.own_lo) t += own_n; }
-        const bool own = t >= a.own_lo && t < a.own_hi;
-        if (!own && !a.Z_other) continue;
-        f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < a.topk; ++s) {
-            const int p = a.pair_pos[t * a.topk + s];
-            if (p < 0) continue;                  // a pair with an invalid expert id contributes nothing
-            const float g = a.gate[t * a.topk + s];
-            const f32x4 y = __builtin_nontemporal_load((const f32x4*)(a.Y + (long long)p * a.N) + j);
-            z = z + g * y;
+        const int grp = (int)(i / n4);
+        const int j = (int)(i - (long long)grp * n4);
+        int tk[U];
+        f32x4 z[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = grp * U + u;                          // place in the order
+            int t = -1;
+            if (v < n_tok) {
+                if (v < own_n) t = a.own_lo + v;
+                else { t = v - own_n; if (t >= a.own_lo) t += own_n; }
+            }
+            tk[u] = t;
+            z[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        f32x4* dst = own ? (f32x4*)(a.Z_own + (long long)(t - a.own_lo) * a.N) + j : (f32x4*)(a.Z_other + (long long)t * a.N) + j;
-        *dst = z;
+        for (int s = 0; s < a.topk; ++s) {
+            int p[U];
+            float g[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                p[u] = tk[u] >= 0 ? a.pair_pos[tk[u] * a.topk + s] : -1;
+                g[u] = tk[u] >= 0 ? a.gate[tk[u] * a.topk + s] : 0.f;
+            }
+            f32x4 y[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)       // (a pair with an invalid expert id has no row: it contributes nothing)
+                y[u] = p[u] >= 0 ? __builtin_nontemporal_load((const f32x4*)(a.Y + (long long)p[u] * a.N) + j) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (p[u] >= 0) z[u] = z[u] + g[u] * y[u];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = tk[u];
+            if (t < 0) continue;
+            const bool own = t >= a.own_lo && t < a.own_hi;
+            f32x4* dst = own ? (f32x4*)(a.Z_own + (long long)(t - a.own_lo) * a.N) + j : (f32x4*)(a.Z_other + (long long)t * a.N) + j;
+            *dst = z[u];
+        }
     }
 }
 
