@@ -60,7 +60,9 @@ enum { AGG_PRODUCER_KERNEL = 0,              /* copy kernel on a few CUs, releas
        AGG_PRODUCER_LOCAL_LAST = 0x200,     /* OR into mode: copy the local shard after the peers' instead of first */
        AGG_PRODUCER_NARROW = 0x400 };       /* OR into mode (copy kernel): workgroups of one wave instead of four, so that
                                                the copy takes a quarter of the register file and issue slots of the compute
-                                               units it shares with the consumer (Section 3.8: few resources for communication) */
+                                               units it shares with the consumer (Section 3.8: few resources for communication);
+                                               when the local shard is not copied first, the first shard to arrive is still
+                                               copied by four-wave workgroups: the consumer's first round of tiles waits for it */
 
 /* One signal word per AGG_SIGNAL_STRIDE int32 (each signal owns a 128-byte line). */
 #define AGG_SIGNAL_STRIDE 32

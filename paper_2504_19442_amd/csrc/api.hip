@@ -438,6 +438,23 @@ int ag_producer_emulate(agg_ctx* c, const void* const* remote_shards, const int*
     }
     if (mode == AGG_PRODUCER_KERNEL) {
         const int nwg = n_workgroups > 0 ? n_workgroups : (c->producer_wgs > 0 ? c->producer_wgs : c->num_cus);
+        if (threads == 64 && a.n_jobs >= 2 && a.rank_of[0] != c->rank) {
+            // Narrow copy, consumer reading its own shard in place: the local shard's tiles occupy only some of the
+            // consumer's workgroups, and the others start on the first shard to arrive -- all of it, in the first round
+            // of tiles.  That shard is therefore copied at full width (it lands in half the time), the rest by
+            // one-wave workgroups.
+            ProducerArgs first = a;
+            first.n_jobs = 1;
+            int rc = hip_fail(launch_producer(first, nwg, 256, st));
+            if (rc != AGG_OK) return rc;
+            ProducerArgs rest = a;
+            rest.n_jobs = a.n_jobs - 1;
+            for (int j = 0; j < rest.n_jobs; ++j) {
+                rest.src[j] = a.src[j + 1];
+                rest.rank_of[j] = a.rank_of[j + 1];
+            }
+            return hip_fail(launch_producer(rest, nwg, threads, st));
+        }
         return hip_fail(launch_producer(a, nwg, threads, st));
     }
     if (mode == AGG_PRODUCER_LINKS) {
