@@ -158,6 +158,25 @@ def test_moe_long_segments_and_more_pairs_than_one_pass_of_the_routing_holds(W, 
         run.close()
 
 
+def test_moe_more_experts_than_routing_workgroups_fit_on_the_chip_at_once():
+    # 1000 experts = 1000 routing workgroups of 16 waves: more than are resident together, so late workgroups read the
+    # counts of workgroups that have long finished.  Most experts get a handful of rows, some none.  Three runs: the
+    # routing's counters go back to rest after every call.
+    sh = wl.MoeShape("moe_many_experts", 23, 1, 5000, 64, 8, 1000, 1)
+    inp = wl.make_moe(sh, x_dist=("int", 2), w_dist=("int", 2))
+    want = oracle.moe_gemm(inp.shards, inp.W_ekn, inp.topk_ids, 0)
+    tok_ref, _, seg_ref = oracle.moe_route(inp.topk_ids, sh.E)
+    run = MoeRun(inp, 0)
+    try:
+        for _ in range(3):
+            Y, tok, seg = run.run()
+            assert np.array_equal(tok, tok_ref)
+            assert np.array_equal(seg.astype(np.int64), seg_ref)
+            assert np.array_equal(Y.cpu().numpy().astype(np.float64), want)
+    finally:
+        run.close()
+
+
 def test_moe_empty_experts_skewed_routing_and_invalid_ids():
     sh = wl.MoeShape("moe_skew", 9, 2, 40, 64, 40, 7, 2)
     inp = wl.make_moe(sh)
